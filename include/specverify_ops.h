@@ -1,0 +1,56 @@
+/*
+ * specverify_ops -- single-operation entry points of the verification library.
+ *
+ * Each runs one stage of the verification pass (see specverify.h for the pass as a whole) on
+ * caller-provided device buffers, so that a stage can be checked against the oracle and timed
+ * on its own.  All pointers are DEVICE pointers unless stated; `stream` is a hipStream_t
+ * (NULL = null stream); calls return after enqueueing.  Return values are sv_status codes.
+ */
+#ifndef SPECVERIFY_OPS_H
+#define SPECVERIFY_OPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+#include "specverify.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Dense projection of the forward pass (the part of parallel verification that is bound by matrix
+ * throughput at large per-worker batch, Section 3 "Challenge #1"):
+ *   out[s][m][n] = sum over k in split s of A[m][k] * W[n][k],   s = 0 .. splits-1
+ * A [M,K] bf16, W [N,K] bf16, out [splits,M,N] fp32 (the consumer adds the splits).
+ * N % 128 == 0, K % (64*splits) == 0.  variant selects the work-group tile (0: 128x128, 1: 64x128,
+ * 2: 256x128 tokens x features). */
+int sv_op_gemm_bf16(const void *A, const void *W, float *out, int M, int N, int K, int splits, int variant,
+                    void *stream);
+
+/* Accept/reject + replacement/bonus draw + chain choice on given target logits (the rule restated at
+ * verify_step).  logits fp32 [B*(1+N*k), V] in verify_step's row order; other arguments as in
+ * verify_step / sv_batch / sv_out.  scratch: sv_op_sample_scratch_bytes(B,N,k) bytes. */
+size_t sv_op_sample_scratch_bytes(int B, int N, int k);
+int sv_op_sample(const float *logits, const int32_t *drafts, const float *draft_probs, const float *uniforms,
+                 const int32_t *draft_lens, int B, int N, int k, int V, int verify_mode, int sample_mode,
+                 float temperature, void *scratch, int32_t *accepted_len, int32_t *out_tokens,
+                 int32_t *best_chain, void *stream);
+
+/* Verify attention alone (the part of parallel verification bound by HBM: every cached K/V byte is read
+ * once for all n rows of a request).  For each listed sequence (HOST array seq_ids[B], live length L_b) the
+ * n query rows q [B*n, n_q_heads, head_dim] (storage type) attend cache entries 0 .. L_b-1 and, of the
+ * entries L_b .. L_b+n-1 (which the caller has written with verify_kv_write: x0, then chain 0's k drafts,
+ * chain 1's ...), x0 and the earlier drafts of their own chain.  out [B*n, n_q_heads*head_dim] (storage
+ * type).  n = 1 + N*k.  Lengths are not changed. */
+int sv_op_attention(sv_ctx *, const int32_t *seq_ids, int B, int n, int k, int layer, const void *q, void *out);
+
+/* Tuning / diagnostic knobs of a context.
+ *   SV_OPT_GEMM_VARIANT  work-group tile of the bf16 projections (0..2, default 0)
+ *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)
+ *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for */
+enum { SV_OPT_GEMM_VARIANT = 1, SV_OPT_ATTN_GENERIC = 2, SV_OPT_ATTN_MIN_ROW_TILES = 3 };
+int sv_set_option(sv_ctx *, int option, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVERIFY_OPS_H */

@@ -144,6 +144,21 @@ class SeqCache:
         self.capacity = capacity
 
 
+def attend(q: np.ndarray, keys: np.ndarray, vals: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Grouped-query attention of n rows over m keys.  q [n, hq, hd]; keys, vals
+    [m, hkv, hd]; mask bool [n, m] (True = row attends key).  Query head h uses
+    kv head h // (hq/hkv).  softmax(q k^T / sqrt(hd)) v, float64.  -> [n, hq, hd]"""
+    n, hq, hd = q.shape
+    group = hq // keys.shape[1]
+    out = np.empty((n, hq, hd), dtype=np.float64)
+    for hh in range(hq):
+        g = hh // group
+        s = (q[:, hh, :] @ keys[:, g, :].T) / np.sqrt(hd)        # [n, m]
+        s = np.where(mask, s, -np.inf)
+        out[:, hh, :] = softmax(s, axis=-1) @ vals[:, g, :]
+    return out
+
+
 def dense_ffn(spec: ModelSpec, a: np.ndarray, w_gate_up: np.ndarray, w_down: np.ndarray) -> np.ndarray:
     """down( silu(gate(a)) * up(a) ); w_gate_up holds the gate rows first,
     then the up rows.  `a` is already rounded to the storage type."""
@@ -188,7 +203,6 @@ def forward(spec: ModelSpec,
     """
     B, n = tokens.shape
     hq, hkv, hd = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
-    group = hq // hkv
     layer_of: Callable[[int], dict] = (
         weights["layers"] if callable(weights["layers"]) else weights["layers"].__getitem__)
 
@@ -215,11 +229,7 @@ def forward(spec: ModelSpec,
             keys = np.asarray(c.k[l][:L + n], dtype=np.float64)          # [L+n, hkv, hd]
             vals = np.asarray(c.v[l][:L + n], dtype=np.float64)
             mask = np.concatenate([np.ones((n, L), dtype=bool), visible[b]], axis=1)   # [n, L+n]
-            for hh in range(hq):
-                g = hh // group
-                s = (q[b, :, hh, :] @ keys[:, g, :].T) / np.sqrt(hd)        # [n, L+n]
-                s = np.where(mask, s, -np.inf)
-                attn[b, :, hh, :] = softmax(s, axis=-1) @ vals[:, g, :]
+            attn[b] = attend(q[b], keys, vals, mask)
         attn = round_to_storage(attn.reshape(B * n, hq * hd), spec.dtype)
         h = h + matmul_wt(attn, lw["wo"])
 

@@ -1,0 +1,8 @@
+"""MI355X-native batched speculative-verification step (C-ABI library + thin binding).
+
+The product is paper_2511_16193_amd/libspecverify.so (HIP, gfx950); this package only
+marshals arguments.  There is no CPU fallback: using the binding without the built
+library raises.
+"""
+from .binding import (Verifier, SvError, lib, load_library, op_gemm_bf16, op_sample, EXPORTS, LIB_PATH,  # noqa: F401
+                      SV_FP32, SV_BF16, SV_GREEDY, SV_STOCHASTIC, SV_INVERSE_CDF, SV_EXP_RACE, SV_OPT_GEMM_VARIANT, SV_OPT_ATTN_GENERIC, SV_OPT_ATTN_MIN_ROW_TILES)

@@ -1,0 +1,292 @@
+"""ctypes binding of libspecverify.so: argument marshalling only.
+
+Every step of the verification pass runs in the library's HIP kernels; torch is
+used here for device allocations and the stream.  The function names mirror
+include/specverify.h.  Importing this module fails loudly if the library has
+not been built (python -m paper_2511_16193_amd.build).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecverify.so")
+
+SV_FP32, SV_BF16 = 0, 1
+SV_GREEDY, SV_STOCHASTIC = 0, 1
+SV_INVERSE_CDF, SV_EXP_RACE = 0, 1
+SV_OPT_GEMM_VARIANT, SV_OPT_ATTN_GENERIC, SV_OPT_ATTN_MIN_ROW_TILES = 1, 2, 3
+
+EXPORTS = [
+    "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
+    "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
+    "verify_kv_read", "verify_prefill", "verify_step",
+    "sv_op_gemm_bf16", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_attention", "sv_set_option",
+]
+
+
+class SvModel(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ff",
+                                         "vocab", "n_experts", "top_k", "d_expert", "dtype")] + \
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+
+
+class SvWeights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")]
+
+
+class SvRuntime(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("max_batch", "max_k", "max_chains", "max_seqs", "page_size", "num_pages",
+                                         "max_pages_per_seq", "verify_mode", "sample_mode")] + \
+               [("temperature", C.c_float), ("kv_pool", C.c_void_p), ("kv_pool_bytes", C.c_size_t),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class SvBatch(C.Structure):
+    _fields_ = [("B", C.c_int32), ("k", C.c_int32), ("N", C.c_int32), ("seq_ids", C.POINTER(C.c_int32)),
+                ("last_tokens", C.c_void_p), ("draft_lens", C.c_void_p)]
+
+
+class SvOut(C.Structure):
+    _fields_ = [("accepted_len", C.c_void_p), ("out_tokens", C.c_void_p), ("best_chain", C.c_void_p),
+                ("logits", C.c_void_p)]
+
+
+def load_library() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_16193_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    lib.verify_kv_pool_bytes.restype = C.c_size_t
+    lib.verify_kv_pool_bytes.argtypes = [C.POINTER(SvModel), C.POINTER(SvRuntime)]
+    lib.verify_workspace_bytes.restype = C.c_size_t
+    lib.verify_workspace_bytes.argtypes = [C.POINTER(SvModel), C.POINTER(SvRuntime)]
+    lib.verify_init.argtypes = [C.POINTER(SvModel), C.POINTER(SvWeights), C.POINTER(SvRuntime), C.c_void_p,
+                                C.POINTER(C.c_void_p)]
+    lib.verify_destroy.argtypes = [C.c_void_p]
+    lib.verify_destroy.restype = None
+    lib.verify_last_error.argtypes = [C.c_void_p]
+    lib.verify_last_error.restype = C.c_char_p
+    lib.verify_seq_add.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    lib.verify_seq_remove.argtypes = [C.c_void_p, C.c_int32]
+    lib.verify_seq_set_len.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    lib.verify_seq_len.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.verify_kv_write.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.verify_kv_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.verify_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.verify_step.argtypes = [C.c_void_p, C.POINTER(SvBatch), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(SvOut)]
+    lib.sv_op_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                    C.c_void_p]
+    lib.sv_op_sample_scratch_bytes.restype = C.c_size_t
+    lib.sv_op_sample_scratch_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
+    lib.sv_op_sample.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 5
+    lib.sv_op_attention.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                    C.c_void_p]
+    lib.sv_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
+    return lib
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+class SvError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"specverify error {code}: {msg}")
+        self.code = code
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream_ptr():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Verifier:
+    """Owns the device buffers a context borrows and forwards calls to the C ABI."""
+
+    def __init__(self, model: dict, weights: dict, *, max_batch: int, max_k: int, max_chains: int = 1,
+                 max_seqs: int | None = None, page_size: int = 64, num_pages: int, max_pages_per_seq: int,
+                 verify_mode: int = SV_STOCHASTIC, sample_mode: int = SV_EXP_RACE, temperature: float = 1.0,
+                 device="cuda:0"):
+        self.lib = lib()
+        self.device = torch.device(device)
+        self.model = dict(model)
+        dt = SV_BF16 if model["dtype"] == "bf16" else SV_FP32
+        self.torch_dtype = torch.bfloat16 if dt == SV_BF16 else torch.float32
+        self.m = SvModel(model["n_layers"], model["d_model"], model["n_q_heads"], model["n_kv_heads"],
+                         model["head_dim"], model["d_ff"], model["vocab"], model.get("n_experts", 0),
+                         model.get("top_k", 0), model.get("d_expert", 0), dt, model["rope_theta"], model["rms_eps"])
+        self.rt = SvRuntime(max_batch, max_k, max_chains, max_seqs or max_batch, page_size, num_pages,
+                            max_pages_per_seq, verify_mode, sample_mode, temperature, None, 0, None, 0)
+        pool_bytes = self.lib.verify_kv_pool_bytes(C.byref(self.m), C.byref(self.rt))
+        ws_bytes = self.lib.verify_workspace_bytes(C.byref(self.m), C.byref(self.rt))
+        if pool_bytes == 0 or ws_bytes == 0:
+            raise SvError(-1, "invalid model / runtime description")
+        self.kv_pool = torch.empty(pool_bytes, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device)
+        self.rt.kv_pool, self.rt.kv_pool_bytes = self.kv_pool.data_ptr(), pool_bytes
+        self.rt.workspace, self.rt.workspace_bytes = self.workspace.data_ptr(), ws_bytes
+
+        self._keep = weights                       # borrowed by the context: keep alive
+        nl = model["n_layers"]
+
+        def arr(name):
+            if name not in weights["layers"][0]:
+                return None
+            a = (C.c_void_p * nl)()
+            for l in range(nl):
+                t = weights["layers"][l][name]
+                assert t.is_cuda and t.is_contiguous() and t.dtype == self.torch_dtype, name
+                a[l] = t.data_ptr()
+            return a
+
+        self._arrs = {n: arr(n) for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")}
+        w = SvWeights(weights["embed"].data_ptr(), weights["lm_head"].data_ptr(), weights["final_norm"].data_ptr(),
+                      *[self._arrs[n] if self._arrs[n] is not None else None
+                        for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")])
+        ctx = C.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = self.lib.verify_init(C.byref(self.m), C.byref(w), C.byref(self.rt), _stream_ptr(), C.byref(ctx))
+        if rc != 0:
+            raise SvError(rc, "verify_init failed")
+        self.ctx = ctx
+        self.vocab = model["vocab"]
+
+    # -- plumbing --
+    def _check(self, rc: int):
+        if rc != 0:
+            raise SvError(rc, self.lib.verify_last_error(self.ctx).decode())
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.lib.verify_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- sequences --
+    def seq_add(self, seq_id: int, cached_len: int):
+        self._check(self.lib.verify_seq_add(self.ctx, seq_id, cached_len))
+
+    def seq_remove(self, seq_id: int):
+        self._check(self.lib.verify_seq_remove(self.ctx, seq_id))
+
+    def seq_set_len(self, seq_id: int, length: int):
+        self._check(self.lib.verify_seq_set_len(self.ctx, seq_id, length))
+
+    def seq_len(self, seq_id: int) -> int:
+        out = C.c_int32()
+        self._check(self.lib.verify_seq_len(self.ctx, seq_id, C.byref(out)))
+        return out.value
+
+    def kv_write(self, seq_id: int, layer: int, pos0: int, k: torch.Tensor, v: torch.Tensor):
+        assert k.dtype == self.torch_dtype and k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        self._check(self.lib.verify_kv_write(self.ctx, seq_id, layer, pos0, k.shape[0], _ptr(k), _ptr(v)))
+
+    def kv_read(self, seq_id: int, layer: int, pos0: int, n: int):
+        shape = (n, self.model["n_kv_heads"], self.model["head_dim"])
+        k = torch.empty(shape, dtype=self.torch_dtype, device=self.device)
+        v = torch.empty(shape, dtype=self.torch_dtype, device=self.device)
+        self._check(self.lib.verify_kv_read(self.ctx, seq_id, layer, pos0, n, _ptr(k), _ptr(v)))
+        return k, v
+
+    def prefill(self, seq_id: int, tokens: torch.Tensor, want_logits: bool = True):
+        tokens = tokens.to(device=self.device, dtype=torch.int32).contiguous()
+        out = torch.empty(self.vocab, dtype=torch.float32, device=self.device) if want_logits else None
+        self._check(self.lib.verify_prefill(self.ctx, seq_id, _ptr(tokens), tokens.numel(), _ptr(out)))
+        return out
+
+    # -- the step --
+    def step(self, seq_ids, last_tokens: torch.Tensor, drafts: torch.Tensor | None, draft_probs: torch.Tensor | None,
+             uniforms: torch.Tensor | None, *, draft_lens: torch.Tensor | None = None, want_logits: bool = False,
+             out: dict | None = None):
+        """drafts int32 [B,N,k]; draft_probs fp32 [B,N,k,V] or None; uniforms fp32 [B,N,k+1]."""
+        B = len(seq_ids)
+        if drafts is None:
+            N, k = 1, 0
+        else:
+            assert drafts.dtype == torch.int32 and drafts.is_contiguous() and drafts.shape[0] == B
+            N, k = drafts.shape[1], drafts.shape[2]
+        assert last_tokens.dtype == torch.int32 and last_tokens.numel() == B
+        if draft_probs is not None:
+            assert draft_probs.dtype == torch.float32 and draft_probs.is_contiguous()
+            assert tuple(draft_probs.shape) == (B, N, k, self.vocab)
+        if uniforms is not None:
+            assert uniforms.dtype == torch.float32 and uniforms.is_contiguous() and tuple(uniforms.shape) == (B, N, k + 1)
+        ids = (C.c_int32 * B)(*[int(s) for s in seq_ids])
+        if out is None:
+            out = {
+                "accepted_len": torch.empty(B, dtype=torch.int32, device=self.device),
+                "out_tokens": torch.empty((B, k + 1), dtype=torch.int32, device=self.device),
+                "best_chain": torch.empty(B, dtype=torch.int32, device=self.device),
+            }
+            if want_logits:
+                out["logits"] = torch.empty((B, 1 + N * k, self.vocab), dtype=torch.float32, device=self.device)
+        batch = SvBatch(B, k, N, ids, last_tokens.data_ptr(), None if draft_lens is None else draft_lens.data_ptr())
+        o = SvOut(out["accepted_len"].data_ptr(), out["out_tokens"].data_ptr(), out["best_chain"].data_ptr(),
+                  out["logits"].data_ptr() if "logits" in out else None)
+        self._check(self.lib.verify_step(self.ctx, C.byref(batch), _ptr(drafts), _ptr(draft_probs), _ptr(uniforms),
+                                         C.byref(o)))
+        return out
+
+    def op_attention(self, seq_ids, n: int, k: int, layer: int, q: torch.Tensor) -> torch.Tensor:
+        """q [B*n, n_q_heads, head_dim] storage type -> [B*n, n_q_heads*head_dim]."""
+        B = len(seq_ids)
+        assert q.dtype == self.torch_dtype and q.is_contiguous() and q.shape[0] == B * n
+        out = torch.empty((B * n, q.shape[1] * q.shape[2]), dtype=self.torch_dtype, device=self.device)
+        ids = (C.c_int32 * B)(*[int(s) for s in seq_ids])
+        self._check(self.lib.sv_op_attention(self.ctx, ids, B, n, k, layer, _ptr(q), _ptr(out)))
+        return out
+
+    def set_option(self, option: int, value: int):
+        self._check(self.lib.sv_set_option(self.ctx, option, value))
+
+
+# ---- single operations ----
+
+def op_gemm_bf16(a: torch.Tensor, w: torch.Tensor, splits: int = 1, variant: int = 0) -> torch.Tensor:
+    """a [M,K] bf16, w [N,K] bf16 -> [splits, M, N] fp32 partial products."""
+    assert a.dtype == torch.bfloat16 and w.dtype == torch.bfloat16 and a.is_contiguous() and w.is_contiguous()
+    M, K = a.shape
+    N = w.shape[0]
+    out = torch.empty((splits, M, N), dtype=torch.float32, device=a.device)
+    rc = lib().sv_op_gemm_bf16(_ptr(a), _ptr(w), _ptr(out), M, N, K, splits, variant, _stream_ptr())
+    if rc != 0:
+        raise SvError(rc, "sv_op_gemm_bf16")
+    return out
+
+
+def op_sample(logits: torch.Tensor, drafts: torch.Tensor, draft_probs, uniforms, *, verify_mode: int,
+              sample_mode: int = SV_EXP_RACE, temperature: float = 1.0, draft_lens=None):
+    """logits fp32 [B, 1+N*k, V]; drafts int32 [B,N,k]."""
+    B, N, k = drafts.shape
+    V = logits.shape[-1]
+    assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.shape[1] == 1 + N * k
+    dev = logits.device
+    scratch = torch.empty(lib().sv_op_sample_scratch_bytes(B, N, k), dtype=torch.uint8, device=dev)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    toks = torch.empty((B, k + 1), dtype=torch.int32, device=dev)
+    best = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib().sv_op_sample(_ptr(logits), _ptr(drafts), _ptr(draft_probs), _ptr(uniforms), _ptr(draft_lens), B, N, k, V,
+                            verify_mode, sample_mode, temperature, _ptr(scratch), _ptr(acc), _ptr(toks), _ptr(best),
+                            _stream_ptr())
+    if rc != 0:
+        raise SvError(rc, "sv_op_sample")
+    return acc, toks, best

@@ -1,0 +1,343 @@
+// Verify attention: the n new rows of every request attend that request's paged KV cache plus the
+// new rows they are allowed to see.  Every cached byte is read once per step however many rows
+// verify against it -- that reuse across the k+1 rows is the saving of parallel verification -- so
+// the kernel is bound by HBM bandwidth and is organised around streaming K/V.
+//
+// bf16 path (head_dim 128).  A work-group owns one (request, kv head, chunk of keys).  All G*n query
+// rows that share the kv head (G = q heads per kv head) are stacked into R tiles of 16 rows.  Each
+// of the 4 waves walks its own 32-key tiles of the chunk; per tile it loads K (32 x 128) and V^T
+// (128 x 32) straight from the page into MFMA operand registers (the next tile's loads are issued
+// before the current tile's math), forms S^T = K Q^T with v_mfma_f32_16x16x32_bf16, runs the online
+// softmax in fp32 on the four keys per row each lane holds, and feeds P^T (as three bf16 terms) back
+// as the B operand of O^T += V^T P^T.  The score tile's register layout (a lane holds 4 consecutive keys of one row, for
+// two 16-key blocks) is used unchanged as the PV operand; the reduction index of that MFMA is only a
+// label, so V^T is simply loaded with the same key order.  Waves are merged through LDS, chunks by
+// a second small kernel (split-KV).
+//
+// Generic path (fp32 models, other head sizes, more than 64 stacked rows): one wave per (row, head),
+// plain online softmax; correct for every shape, not tuned.
+#include <math.h>
+#include <algorithm>
+#include "common.h"
+#include "kernels.h"
+
+namespace sv {
+
+constexpr int HD = 128;
+constexpr int TILE_KEYS = 32;
+
+struct KTile { u32x4 k[2][4]; u32x2 v[8][2]; };
+
+template <int R>
+__global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
+    const int chunk = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+    const int seq = a.batch_seq[b];
+    const int L = a.seq_len[seq];
+    const int total = L + a.n;
+    const int kbeg = chunk * a.chunk_keys;
+    if (kbeg >= total) return;
+    const int kend = min(kbeg + a.chunk_keys, total);
+    const int G = a.Hq / a.Hkv, rows = G * a.n;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+    const bf16_t* pool = reinterpret_cast<const bf16_t*>(a.pool);
+    const int32_t* pages = a.page_table + (int64_t)seq * a.max_pages_per_seq;
+
+    // Q^T operand: lane holds row rt*16 + l16, head_dim slice kk*32 + lg*8 .. +8
+    u32x4 qf[R][4];
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+        const int r = rt * 16 + l16;
+        const bool ok = r < rows;
+        const int j = ok ? r / G : 0, hl = ok ? r % G : 0;
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (((int64_t)b * a.n + j) * a.Hq + hkv * G + hl) * HD;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qf[rt][kk] = ok ? *reinterpret_cast<const u32x4*>(qp + kk * 32 + lg * 8) : u32x4{0, 0, 0, 0};
+    }
+
+    // A row sees every cached key, x0 (key L) and the drafts of its own chain up to itself: the keys
+    // [vis_lo, vis_hi).  Rows of x0 and padding rows get an empty interval.
+    int vis_lo[R], vis_hi[R];
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+        const int r = rt * 16 + l16;
+        const int j = r < rows ? r / G : 0;
+        vis_lo[rt] = j > 0 ? L + 1 + row_chain(j, a.k) * a.k : 0;
+        vis_hi[rt] = j > 0 ? vis_lo[rt] + row_index_in_chain(j, a.k) : 0;
+    }
+
+    floatx4 o[8][R];
+    float m_run[R], l_run[R];
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+        m_run[rt] = -INFINITY;
+        l_run[rt] = 0.f;
+#pragma unroll
+        for (int ht = 0; ht < 8; ++ht) o[ht][rt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    auto load_tile = [&](int key0, KTile& t) {
+        const int page = pages[key0 / a.geom.page_size];
+        const int off = key0 % a.geom.page_size;
+        const bf16_t* kp = pool + kv_k_index(a.geom, a.layer, page, hkv, off, 0);
+        const bf16_t* vp = pool + kv_v_index(a.geom, a.layer, page, hkv, off, 0);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                t.k[kb][kk] = *reinterpret_cast<const u32x4*>(kp + (kb * 16 + l16) * HD + kk * 32 + lg * 8);
+#pragma unroll
+        for (int ht = 0; ht < 8; ++ht)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                t.v[ht][hf] = *reinterpret_cast<const u32x2*>(vp + (ht * 16 + l16) * kVBlk + hf * 16 + lg * 4);
+    };
+
+    const int ntiles = (kend - kbeg + TILE_KEYS - 1) / TILE_KEYS;
+    KTile cur, nxt;
+    int it = wave;
+    if (it < ntiles) load_tile(kbeg + it * TILE_KEYS, cur);
+    for (; it < ntiles; it += 4) {
+        const int key0 = kbeg + it * TILE_KEYS;
+        if (it + 4 < ntiles) load_tile(key0 + 4 * TILE_KEYS, nxt);
+
+        // S^T = K Q^T : s[kb][rt][i] <-> key key0 + kb*16 + 4*lg + i, row rt*16 + l16
+        floatx4 s[2][R];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int rt = 0; rt < R; ++rt) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, cur.k[kb][kk]), __builtin_bit_cast(bf16x8, qf[rt][kk]), acc, 0, 0, 0);
+                s[kb][rt] = acc * scale_log2e;
+            }
+        if (key0 + TILE_KEYS > L) {   // tile touches the new rows or the end: apply visibility
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int rt = 0; rt < R; ++rt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int key = key0 + kb * 16 + 4 * lg + i;
+                        // bitwise, not short-circuit: this must stay a compare + select chain.  (With
+                        // && / || the compiler built branches here and dropped the value of the first
+                        // element on the path "beyond L, yet visible".)
+                        const bool vis = (key <= L) | ((key >= vis_lo[rt]) & (key < vis_hi[rt]));
+                        s[kb][rt][i] = vis ? s[kb][rt][i] : -INFINITY;
+                    }
+        }
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+            float mx = fmaxf(fmaxf(fmaxf(s[0][rt][0], s[0][rt][1]), fmaxf(s[0][rt][2], s[0][rt][3])),
+                             fmaxf(fmaxf(s[1][rt][0], s[1][rt][1]), fmaxf(s[1][rt][2], s[1][rt][3])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[rt], mx);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = exp2f(m_run[rt] - m_safe);
+            m_run[rt] = m_new;
+            float p[8];
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                p[i] = exp2f(s[0][rt][i] - m_safe);
+                p[4 + i] = exp2f(s[1][rt][i] - m_safe);
+                psum += p[i] + p[4 + i];
+            }
+            l_run[rt] = l_run[rt] * alpha + psum;
+            // P goes to the MFMA as three bf16 terms (24 significant bits in all).  One bf16 term would
+            // leave a 2^-9 relative error in the output however many keys there are (V has zero mean, so
+            // the output is as small as the error's random walk); two terms leave 2^-17, still enough to
+            // move every few-hundredth output across a bf16 rounding boundary.
+            u32x4 pf[3];
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                uint32_t w[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bf16_t a0 = f2bf(p[2 * i]), a1 = f2bf(p[2 * i + 1]);
+                    p[2 * i] -= bf2f(a0);
+                    p[2 * i + 1] -= bf2f(a1);
+                    w[i] = (uint32_t)a0 | ((uint32_t)a1 << 16);
+                }
+                pf[t] = u32x4{w[0], w[1], w[2], w[3]};
+            }
+#pragma unroll
+            for (int ht = 0; ht < 8; ++ht) {
+                o[ht][rt] = o[ht][rt] * alpha;
+                u32x4 vf = {cur.v[ht][0][0], cur.v[ht][0][1], cur.v[ht][1][0], cur.v[ht][1][1]};
+#pragma unroll
+                for (int t = 2; t >= 0; --t)
+                    o[ht][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                                        __builtin_bit_cast(bf16x8, pf[t]), o[ht][rt], 0, 0, 0);
+            }
+        }
+        cur = nxt;
+    }
+
+    // ---- merge the four waves of the group through LDS ----
+    constexpr int RP = 16 * R;
+    __shared__ float m_sh[4][RP], l_sh[4][RP];
+    __shared__ float o_sh[HD][RP + 1];
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+        float l = l_run[rt];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (lg == 0) {
+            m_sh[wave][rt * 16 + l16] = m_run[rt];
+            l_sh[wave][rt * 16 + l16] = l;
+        }
+    }
+    __syncthreads();
+    float fac[R], m_all[R], l_all[R];
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+        const int r = rt * 16 + l16;
+        float mm = fmaxf(fmaxf(m_sh[0][r], m_sh[1][r]), fmaxf(m_sh[2][r], m_sh[3][r]));
+        const float ms = mm == -INFINITY ? 0.f : mm;
+        float ll = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) ll += l_sh[w][r] * exp2f(m_sh[w][r] - ms);
+        fac[rt] = exp2f(m_run[rt] - ms);
+        m_all[rt] = mm;
+        l_all[rt] = ll;
+    }
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int rt = 0; rt < R; ++rt)
+#pragma unroll
+                for (int ht = 0; ht < 8; ++ht)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float* dst = &o_sh[ht * 16 + 4 * lg + i][rt * 16 + l16];
+                        const float v = o[ht][rt][i] * fac[rt];
+                        *dst = w == 0 ? v : *dst + v;
+                    }
+        }
+        __syncthreads();
+    }
+    const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.max_chunks + chunk) * RP;
+    for (int e = tid; e < rows * HD; e += 256) {
+        const int r = e / HD, d = e % HD;
+        a.part_o[(pbase + r) * HD + d] = o_sh[d][r];
+    }
+    if (wave == 0 && lg == 0) {
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+            const int r = rt * 16 + l16;
+            a.part_ml[(pbase + r) * 2] = m_all[rt];
+            a.part_ml[(pbase + r) * 2 + 1] = l_all[rt];
+        }
+    }
+}
+
+// Combine the chunk partials of one (row, q head): out = sum_c 2^(m_c - M) O_c / sum_c 2^(m_c - M) l_c.
+__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, int rows_pad) {
+    const int t = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+    const int b = t / a.n, j = t % a.n;
+    const int G = a.Hq / a.Hkv, hkv = h / G, r = j * G + h % G;
+    const int total = a.seq_len[a.batch_seq[b]] + a.n;
+    const int nch = (total + a.chunk_keys - 1) / a.chunk_keys;
+    const int64_t base = ((int64_t)b * a.Hkv + hkv) * a.max_chunks;
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((base + c) * rows_pad + r) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < nch; ++c) {
+        const int64_t pr = (base + c) * rows_pad + r;
+        const float f = exp2f(a.part_ml[pr * 2] - M);
+        den += f * a.part_ml[pr * 2 + 1];
+        num += f * a.part_o[pr * HD + d];
+    }
+    reinterpret_cast<bf16_t*>(a.out)[((int64_t)t * a.Hq + h) * HD + d] = f2bf(num / den);
+}
+
+// Generic path: one wave per (new row, q head).  Lane-strided keys, per-lane online softmax with the
+// accumulator in registers, wave reduction at the end.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void attn_generic_kernel(AttnArgs a, float scale) {
+    const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int b = t / a.n, j = t % a.n;
+    const int seq = a.batch_seq[b];
+    const int L = a.seq_len[seq], total = L + a.n;
+    const int hkv = h / (a.Hq / a.Hkv);
+    const int32_t* pages = a.page_table + (int64_t)seq * a.max_pages_per_seq;
+    const T* pool = reinterpret_cast<const T*>(a.pool);
+    __shared__ float q[D];
+    for (int d = lane; d < D; d += 64) q[d] = Store<T>::load(reinterpret_cast<const T*>(a.q) + ((int64_t)t * a.Hq + h) * D + d);
+    __syncthreads();
+    float m = -INFINITY, l = 0.f, acc[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) acc[d] = 0.f;
+    for (int key = lane; key < total; key += 64) {
+        if (key >= L && !row_sees(j, key - L, a.k)) continue;
+        const int page = pages[key / a.geom.page_size], tok = key % a.geom.page_size;
+        float s = 0.f;
+#pragma unroll 8
+        for (int d = 0; d < D; ++d) s = fmaf(q[d], Store<T>::load(pool + kv_k_index(a.geom, a.layer, page, hkv, tok, d)), s);
+        s *= scale;
+        const float mn = fmaxf(m, s);
+        const float alpha = expf(m - mn), p = expf(s - mn);
+        l = l * alpha + p;
+#pragma unroll 8
+        for (int d = 0; d < D; ++d)
+            acc[d] = acc[d] * alpha + p * Store<T>::load(pool + kv_v_index(a.geom, a.layer, page, hkv, tok, d));
+        m = mn;
+    }
+    const float M = wave_max(m);
+    const float f = m == -INFINITY ? 0.f : expf(m - M);
+    const float den = wave_sum(l * f);
+    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)t * a.Hq + h) * D;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const float v = wave_sum(acc[d] * f);
+        if (lane == 0) Store<T>::store(out + d, v / den);
+    }
+}
+
+int attn_rows_pad(int n, int group) {
+    const int rows = n * group;
+    if (rows > 64) return 0;
+    return (rows + 15) / 16 * 16;
+}
+
+hipError_t attention(const AttnArgs& a, hipStream_t st) {
+    const float scale = 1.0f / sqrtf((float)a.hd);
+    const int G = a.Hq / a.Hkv;
+    const int rp = (!a.force_generic && a.dtype == 1 && a.hd == HD && a.geom.page_size % TILE_KEYS == 0 && a.chunk_keys % 128 == 0)
+                       ? attn_rows_pad(a.n, G) : 0;
+    if (rp) {
+        const float sl2 = scale * 1.44269504088896340736f;
+        dim3 grid(a.max_chunks, a.Hkv, a.B);
+        switch (std::max(rp / 16, a.min_row_tiles)) {
+            case 1: hipLaunchKernelGGL(attn_bf16_kernel<1>, grid, dim3(256), 0, st, a, sl2); break;
+            case 2: hipLaunchKernelGGL(attn_bf16_kernel<2>, grid, dim3(256), 0, st, a, sl2); break;
+            case 3: hipLaunchKernelGGL(attn_bf16_kernel<3>, grid, dim3(256), 0, st, a, sl2); break;
+            default: hipLaunchKernelGGL(attn_bf16_kernel<4>, grid, dim3(256), 0, st, a, sl2); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, a.Hq), dim3(HD), 0, st, a, std::max(rp, 16 * a.min_row_tiles));
+        return hipGetLastError();
+    }
+    dim3 grid(a.B * a.n, a.Hq);
+    if (a.dtype == 1 && a.hd == 128)
+        hipLaunchKernelGGL((attn_generic_kernel<bf16_t, 128>), grid, dim3(64), 0, st, a, scale);
+    else if (a.dtype == 1 && a.hd == 64)
+        hipLaunchKernelGGL((attn_generic_kernel<bf16_t, 64>), grid, dim3(64), 0, st, a, scale);
+    else if (a.dtype == 0 && a.hd == 128)
+        hipLaunchKernelGGL((attn_generic_kernel<float, 128>), grid, dim3(64), 0, st, a, scale);
+    else if (a.dtype == 0 && a.hd == 64)
+        hipLaunchKernelGGL((attn_generic_kernel<float, 64>), grid, dim3(64), 0, st, a, scale);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace sv

@@ -1,0 +1,81 @@
+// Shared device-side definitions for the gfx950 kernels of the verification step.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sv {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kVBlk = 32;          // keys per transposed-V sub-block inside a KV page
+
+typedef uint16_t bf16_t;           // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// float -> bf16, round to nearest even (finite inputs).
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// Storage-type traits: T is float (fp32 model) or bf16_t (bf16 model).
+template <typename T> struct Store;
+template <> struct Store<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Store<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(*p); }
+    static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f2bf(v); }
+};
+
+// ---- paged KV layout -------------------------------------------------------
+// pool[layer][page][K | V][kv_head]:
+//   K block: [page_size][head_dim]                      (token major)
+//   V block: [page_size / kVBlk][head_dim][kVBlk]       (transposed in sub-blocks of 32 keys, so a
+//            32-key tile of V^T is one contiguous region with the keys of one head_dim row adjacent)
+struct KvGeom {
+    int n_kv_heads, head_dim, page_size;
+    int64_t page_elems;    // 2 * n_kv_heads * page_size * head_dim
+    int64_t layer_elems;   // num_pages * page_elems
+};
+__host__ __device__ __forceinline__ int64_t kv_k_index(const KvGeom& g, int layer, int page, int head, int tok, int dim) {
+    return (int64_t)layer * g.layer_elems + (int64_t)page * g.page_elems +
+           ((int64_t)head * g.page_size + tok) * g.head_dim + dim;
+}
+__host__ __device__ __forceinline__ int64_t kv_v_index(const KvGeom& g, int layer, int page, int head, int tok, int dim) {
+    return (int64_t)layer * g.layer_elems + (int64_t)page * g.page_elems +
+           (int64_t)g.n_kv_heads * g.page_size * g.head_dim +
+           ((int64_t)head * g.page_size) * g.head_dim +
+           ((int64_t)(tok / kVBlk) * g.head_dim + dim) * kVBlk + (tok % kVBlk);
+}
+
+// Index of new row j (0 = x0, then chain 0's drafts, chain 1's ...) -> chain, index in chain.
+__host__ __device__ __forceinline__ int row_chain(int j, int k) { return j == 0 ? -1 : (j - 1) / k; }
+__host__ __device__ __forceinline__ int row_index_in_chain(int j, int k) { return j == 0 ? 0 : (j - 1) % k + 1; }
+// Does new row i attend new row j?  (x0, and the earlier drafts of its own chain.)
+__host__ __device__ __forceinline__ bool row_sees(int i, int j, int k) {
+    if (j == 0) return true;
+    if (i == 0) return false;
+    return (i - 1) / k == (j - 1) / k && j <= i;
+}
+
+template <typename T> __device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { T w = __shfl_xor(v, o); v = w > v ? w : v; }
+    return v;
+}
+template <typename T> __device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+}  // namespace sv

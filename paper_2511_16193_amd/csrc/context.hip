@@ -1,0 +1,580 @@
+// C ABI of the verification step: context, host-side page bookkeeping, and the sequence of kernel
+// launches that makes up one parallel verification pass (declared in include/specverify.h).
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/specverify.h"
+#include "../../include/specverify_ops.h"
+#include "kernels.h"
+
+using namespace sv;
+
+namespace {
+
+constexpr int kRing = 8;              // pinned staging slots for per-step host -> device metadata
+constexpr int kMaxSplits = 8;
+constexpr int kChunkKeys = 1024;      // keys per split-KV chunk of the bf16 attention
+
+struct SeqState {
+    bool live = false;
+    int len_ub = 0;                   // host upper bound of the live length
+    std::vector<int32_t> pages;
+};
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+int pick_splits(int M, int N, int K) {
+    // enough work-groups to cover the 256 CUs about twice; the reduction range stays a multiple of 64
+    const int tiles = ((M + 127) / 128) * (N / 128);
+    int s = 1;
+    while (s < kMaxSplits && tiles * s < 512 && K % (64 * s * 2) == 0) s *= 2;
+    return s;
+}
+
+struct Layout {                       // byte offsets into the workspace
+    size_t seq_len, page_table, batch_seq, upd, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
+    size_t rope, row_stat, h, a_norm, q, attn, part, act, logits, part_o, part_ml, total;
+    int T, rows_pad, max_chunks;
+};
+
+bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
+    if (r.max_batch <= 0 || r.max_k < 0 || r.max_chains <= 0 || r.max_seqs <= 0 || r.page_size <= 0 ||
+        r.page_size % kVBlk != 0 || r.num_pages <= 0 || r.max_pages_per_seq <= 0)
+        return false;
+    const size_t es = m.dtype == SV_BF16 ? 2 : 4;
+    const int T = r.max_batch * (1 + r.max_chains * r.max_k);
+    const int qw = m.n_q_heads * m.head_dim, qkvw = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    const int F = m.n_experts ? m.d_expert : m.d_ff;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+    L.T = T;
+    L.seq_len = take(sizeof(int32_t) * r.max_seqs);
+    L.page_table = take(sizeof(int32_t) * (size_t)r.max_seqs * r.max_pages_per_seq);
+    L.batch_seq = take(sizeof(int32_t) * r.max_batch);
+    L.upd = take(sizeof(int32_t) * 3 * (size_t)r.max_batch * 8);
+    L.row_tok = take(sizeof(int32_t) * T);
+    L.row_pos = take(sizeof(int32_t) * T);
+    L.row_slot = take(sizeof(int32_t) * T);
+    L.chain_acc = take(sizeof(int32_t) * r.max_batch * r.max_chains);
+    L.chain_tok = take(sizeof(int32_t) * r.max_batch * r.max_chains);
+    L.chain_row = take(sizeof(int32_t) * r.max_batch * r.max_chains);
+    L.rope = take(sizeof(float) * (size_t)T * m.head_dim);
+    L.row_stat = take(sizeof(float) * 4 * T);
+    L.h = take(sizeof(float) * (size_t)T * m.d_model);
+    L.a_norm = take(es * (size_t)T * m.d_model);
+    L.q = take(es * (size_t)T * qw);
+    L.attn = take(es * (size_t)T * qw);
+    // split-K partial products: the largest splits * rows * features any projection can ask for
+    size_t part = 0;
+    const int shapes[4][2] = {{qkvw, m.d_model}, {m.d_model, qw}, {2 * F, m.d_model}, {m.d_model, F}};
+    for (int tm = 1; tm <= (T + 127) / 128; ++tm) {
+        const int M = std::min(tm * 128, T);
+        for (auto& sh : shapes)
+            part = std::max(part, (size_t)(m.dtype == SV_BF16 ? pick_splits(M, sh[0], sh[1]) : 1) * M * sh[0]);
+    }
+    L.part = take(sizeof(float) * part);
+    L.act = take(es * (size_t)T * F);
+    L.logits = take(sizeof(float) * (size_t)T * m.vocab);
+    const int G = m.n_q_heads / std::max(1, m.n_kv_heads);
+    L.rows_pad = 64;
+    L.max_chunks = (int)(((size_t)r.max_pages_per_seq * r.page_size + kChunkKeys - 1) / kChunkKeys);
+    (void)G;
+    L.part_o = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * m.head_dim);
+    L.part_ml = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * 2);
+    L.total = o;
+    return true;
+}
+
+bool model_ok(const sv_model& m) {
+    return m.n_layers > 0 && m.d_model > 0 && m.n_q_heads > 0 && m.n_kv_heads > 0 && m.head_dim > 0 &&
+           m.head_dim % 2 == 0 && m.vocab > 0 && m.n_q_heads % m.n_kv_heads == 0 &&
+           (m.dtype == SV_FP32 || m.dtype == SV_BF16) && (m.n_experts > 0 || m.d_ff > 0);
+}
+
+__global__ void apply_page_updates_kernel(int32_t* page_table, int mpps, const int32_t* upd, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) page_table[(int64_t)upd[3 * i] * mpps + upd[3 * i + 1]] = upd[3 * i + 2];
+}
+
+}  // namespace
+
+struct sv_ctx {
+    sv_model model;
+    sv_runtime rt;
+    std::vector<const void*> ln1, wqkv, wo, ln2, wgu, wdown, wrouter;
+    const void *embed, *lm_head, *final_norm;
+    hipStream_t stream;
+    Layout lay;
+    KvGeom geom;
+    char* ws;
+    std::vector<SeqState> seqs;
+    std::vector<int32_t> free_pages;
+    int32_t* staging[kRing];
+    hipEvent_t staged[kRing];
+    bool staged_valid[kRing];
+    int ring_pos;
+    int gemm_variant;
+    bool attn_generic;
+    int attn_min_rt;
+    std::string err;
+
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+    int fail(int code, const char* fmt, ...) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        err = buf;
+        return code;
+    }
+    int hip(hipError_t e, const char* what) {
+        if (e == hipSuccess) return SV_OK;
+        return fail(SV_EHIP, "%s: %s", what, hipGetErrorString(e));
+    }
+};
+
+#define SV_TRY(expr)                    \
+    do {                                \
+        int _rc = (expr);               \
+        if (_rc != SV_OK) return _rc;   \
+    } while (0)
+#define SV_HIP(ctx, expr) SV_TRY((ctx)->hip((expr), #expr))
+
+static KvGeom make_geom(const sv_model& m, const sv_runtime& r) {
+    KvGeom g;
+    g.n_kv_heads = m.n_kv_heads;
+    g.head_dim = m.head_dim;
+    g.page_size = r.page_size;
+    g.page_elems = (int64_t)2 * m.n_kv_heads * r.page_size * m.head_dim;
+    g.layer_elems = (int64_t)r.num_pages * g.page_elems;
+    return g;
+}
+
+extern "C" size_t verify_kv_pool_bytes(const sv_model* m, const sv_runtime* r) {
+    if (!m || !r || !model_ok(*m) || r->num_pages <= 0 || r->page_size <= 0) return 0;
+    const KvGeom g = make_geom(*m, *r);
+    return (size_t)m->n_layers * g.layer_elems * (m->dtype == SV_BF16 ? 2 : 4);
+}
+
+extern "C" size_t verify_workspace_bytes(const sv_model* m, const sv_runtime* r) {
+    Layout L;
+    if (!m || !r || !model_ok(*m) || !make_layout(*m, *r, L)) return 0;
+    return L.total;
+}
+
+extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runtime* r, void* hip_stream, sv_ctx** out) {
+    if (!m || !w || !r || !out) return SV_EINVAL;
+    *out = nullptr;
+    Layout L;
+    if (!model_ok(*m) || !make_layout(*m, *r, L)) return SV_EINVAL;
+    if (!r->kv_pool || !r->workspace || r->kv_pool_bytes < verify_kv_pool_bytes(m, r) || r->workspace_bytes < L.total ||
+        ((uintptr_t)r->kv_pool & 255) || ((uintptr_t)r->workspace & 255))
+        return SV_EINVAL;
+    if (!(r->temperature > 0.f) || r->verify_mode < 0 || r->verify_mode > 1 || r->sample_mode < 0 || r->sample_mode > 1)
+        return SV_EINVAL;
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->ln1 || !w->wqkv || !w->wo || !w->ln2 || !w->w_gate_up || !w->w_down)
+        return SV_EINVAL;
+    if (m->n_experts > 0) return SV_EUNSUPPORTED;                 // mixture-of-experts FFN: not built yet
+    if (m->head_dim != 64 && m->head_dim != 128) return SV_EUNSUPPORTED;
+    if (m->dtype == SV_BF16) {
+        const int qw = m->n_q_heads * m->head_dim, qkvw = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
+        if (!gemm_bf16_shape_ok(qkvw, m->d_model, 1) || !gemm_bf16_shape_ok(m->d_model, qw, 1) ||
+            !gemm_bf16_shape_ok(2 * m->d_ff, m->d_model, 1) || !gemm_bf16_shape_ok(m->d_model, m->d_ff, 1) ||
+            !gemm_bf16_shape_ok(m->vocab, m->d_model, 1))
+            return SV_EUNSUPPORTED;                                // GEMM N must be a multiple of 128, K of 64
+    }
+    sv_ctx* c = new sv_ctx();
+    c->model = *m;
+    c->rt = *r;
+    c->lay = L;
+    c->geom = make_geom(*m, *r);
+    c->ws = reinterpret_cast<char*>(r->workspace);
+    c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    c->embed = w->embed; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
+    for (int l = 0; l < m->n_layers; ++l) {
+        if (!w->ln1[l] || !w->wqkv[l] || !w->wo[l] || !w->ln2[l] || !w->w_gate_up[l] || !w->w_down[l]) {
+            delete c;
+            return SV_EINVAL;
+        }
+        c->ln1.push_back(w->ln1[l]); c->wqkv.push_back(w->wqkv[l]); c->wo.push_back(w->wo[l]);
+        c->ln2.push_back(w->ln2[l]); c->wgu.push_back(w->w_gate_up[l]); c->wdown.push_back(w->w_down[l]);
+        c->wrouter.push_back(w->w_router ? w->w_router[l] : nullptr);
+    }
+    c->seqs.resize(r->max_seqs);
+    c->free_pages.resize(r->num_pages);
+    for (int i = 0; i < r->num_pages; ++i) c->free_pages[i] = r->num_pages - 1 - i;   // pop_back yields 0,1,2..
+    c->ring_pos = 0;
+    c->gemm_variant = 0;
+    c->attn_generic = false;
+    c->attn_min_rt = 1;
+    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8) + 8;
+    for (int i = 0; i < kRing; ++i) { c->staging[i] = nullptr; c->staged[i] = nullptr; c->staged_valid[i] = false; }
+    for (int i = 0; i < kRing; ++i) {
+        if (hipHostMalloc(reinterpret_cast<void**>(&c->staging[i]), slot_ints * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
+            hipEventCreateWithFlags(&c->staged[i], hipEventDisableTiming) != hipSuccess) {
+            verify_destroy(c);
+            return SV_EHIP;
+        }
+    }
+    // lengths and page table start at zero; an uninitialised pool could hold NaN patterns, which a
+    // masked-out key would still feed into the PV product (0 * NaN), so the pool is cleared once.
+    if (hipMemsetAsync(c->ws, 0, L.rope, c->stream) != hipSuccess ||
+        hipMemsetAsync(r->kv_pool, 0, verify_kv_pool_bytes(m, r), c->stream) != hipSuccess) {
+        verify_destroy(c);
+        return SV_EHIP;
+    }
+    *out = c;
+    return SV_OK;
+}
+
+extern "C" void verify_destroy(sv_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (int i = 0; i < kRing; ++i) {
+        if (c->staging[i]) (void)hipHostFree(c->staging[i]);
+        if (c->staged[i]) (void)hipEventDestroy(c->staged[i]);
+    }
+    delete c;
+}
+
+extern "C" const char* verify_last_error(const sv_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+// ------------------------------------------------------------ sequences ---
+
+static int pages_for(const sv_ctx* c, int len) { return (len + c->rt.page_size - 1) / c->rt.page_size; }
+
+extern "C" int verify_seq_add(sv_ctx* c, int32_t id, int32_t cached_len) {
+    if (!c) return SV_EINVAL;
+    if (id < 0 || id >= c->rt.max_seqs) return c->fail(SV_ENOSEQ, "sequence id %d out of range", id);
+    if (c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d already live", id);
+    const int need = pages_for(c, cached_len);
+    if (cached_len < 0 || need > c->rt.max_pages_per_seq)
+        return c->fail(SV_EINVAL, "cached_len %d exceeds max_pages_per_seq", cached_len);
+    if (need > (int)c->free_pages.size()) return c->fail(SV_ENOPAGES, "need %d pages, %zu free", need, c->free_pages.size());
+    SeqState& s = c->seqs[id];
+    std::vector<int32_t> pages;
+    for (int i = 0; i < need; ++i) { pages.push_back(c->free_pages.back()); c->free_pages.pop_back(); }
+    hipError_t e = hipSuccess;
+    if (need) e = hipMemcpyAsync(c->at<int32_t>(c->lay.page_table) + (size_t)id * c->rt.max_pages_per_seq, pages.data(),
+                                 need * sizeof(int32_t), hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = set_i32(c->at<int32_t>(c->lay.seq_len) + id, cached_len, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);     // `pages` is a temporary
+    if (e != hipSuccess) {
+        for (int32_t p : pages) c->free_pages.push_back(p);
+        return c->hip(e, "verify_seq_add");
+    }
+    s.live = true; s.len_ub = cached_len; s.pages.swap(pages);
+    return SV_OK;
+}
+
+extern "C" int verify_seq_remove(sv_ctx* c, int32_t id) {
+    if (!c) return SV_EINVAL;
+    if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+    SeqState& s = c->seqs[id];
+    for (int32_t p : s.pages) c->free_pages.push_back(p);
+    s = SeqState();
+    return SV_OK;
+}
+
+extern "C" int verify_seq_set_len(sv_ctx* c, int32_t id, int32_t len) {
+    if (!c) return SV_EINVAL;
+    if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+    SeqState& s = c->seqs[id];
+    if (len < 0 || len > (int)s.pages.size() * c->rt.page_size)
+        return c->fail(SV_EINVAL, "length %d beyond the %zu pages held", len, s.pages.size());
+    SV_HIP(c, set_i32(c->at<int32_t>(c->lay.seq_len) + id, len, c->stream));
+    s.len_ub = len;
+    return SV_OK;
+}
+
+extern "C" int verify_seq_len(sv_ctx* c, int32_t id, int32_t* len_out) {
+    if (!c || !len_out) return SV_EINVAL;
+    if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+    int32_t len = 0;
+    SV_HIP(c, hipMemcpyAsync(&len, c->at<int32_t>(c->lay.seq_len) + id, sizeof len, hipMemcpyDeviceToHost, c->stream));
+    SV_HIP(c, hipStreamSynchronize(c->stream));
+    SeqState& s = c->seqs[id];
+    s.len_ub = len;
+    const int keep = pages_for(c, len);
+    while ((int)s.pages.size() > keep) { c->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
+    *len_out = len;
+    return SV_OK;
+}
+
+static int kv_io(sv_ctx* c, int32_t id, int32_t layer, int32_t pos0, int32_t n, void* k, void* v, bool to_pool) {
+    if (!c || !k || !v) return SV_EINVAL;
+    if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+    if (layer < 0 || layer >= c->model.n_layers || pos0 < 0 || n < 0 ||
+        pos0 + n > (int)c->seqs[id].pages.size() * c->rt.page_size)
+        return c->fail(SV_EINVAL, "kv range [%d,%d) of layer %d outside the pages held", pos0, pos0 + n, layer);
+    SV_HIP(c, kv_copy(c->rt.kv_pool, c->geom, layer, c->at<int32_t>(c->lay.page_table) + (size_t)id * c->rt.max_pages_per_seq,
+                      pos0, n, k, v, c->model.dtype, to_pool, c->stream));
+    return SV_OK;
+}
+extern "C" int verify_kv_write(sv_ctx* c, int32_t id, int32_t layer, int32_t pos0, int32_t n, const void* k, const void* v) {
+    return kv_io(c, id, layer, pos0, n, const_cast<void*>(k), const_cast<void*>(v), true);
+}
+extern "C" int verify_kv_read(sv_ctx* c, int32_t id, int32_t layer, int32_t pos0, int32_t n, void* k, void* v) {
+    return kv_io(c, id, layer, pos0, n, k, v, false);
+}
+
+// ---------------------------------------------------------- forward pass ---
+
+// Make sure every listed sequence holds pages for `extra` more entries; push ids and new page-table
+// entries to the device.  Nothing changes if the pool cannot cover the whole batch.
+static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
+    int need_total = 0;
+    for (int b = 0; b < B; ++b) {
+        const int id = ids[b];
+        if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+        for (int b2 = 0; b2 < b; ++b2)
+            if (ids[b2] == id) return c->fail(SV_ENOSEQ, "sequence id %d appears twice in the batch", id);
+        const int need = pages_for(c, c->seqs[id].len_ub + extra);
+        if (need > c->rt.max_pages_per_seq) return c->fail(SV_ENOPAGES, "sequence %d would exceed max_pages_per_seq", id);
+        need_total += std::max(0, need - (int)c->seqs[id].pages.size());
+    }
+    if (need_total > (int)c->free_pages.size())
+        return c->fail(SV_ENOPAGES, "need %d more pages, %zu free", need_total, c->free_pages.size());
+    if (need_total > B * 8) return c->fail(SV_EINVAL, "more than %d new pages in one step", B * 8);
+
+    const int slot = c->ring_pos;
+    if (c->staged_valid[slot]) SV_HIP(c, hipEventSynchronize(c->staged[slot]));
+    int32_t* st = c->staging[slot];
+    int nupd = 0;
+    int32_t* upd = st + B;
+    for (int b = 0; b < B; ++b) {
+        SeqState& s = c->seqs[ids[b]];
+        st[b] = ids[b];
+        const int need = pages_for(c, s.len_ub + extra);
+        while ((int)s.pages.size() < need) {
+            const int32_t p = c->free_pages.back();
+            c->free_pages.pop_back();
+            upd[3 * nupd] = ids[b]; upd[3 * nupd + 1] = (int32_t)s.pages.size(); upd[3 * nupd + 2] = p;
+            s.pages.push_back(p);
+            ++nupd;
+        }
+    }
+    SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.batch_seq), st, B * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    if (nupd) {
+        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.upd), upd, 3 * nupd * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+        hipLaunchKernelGGL(apply_page_updates_kernel, dim3((nupd + 63) / 64), dim3(64), 0, c->stream,
+                           c->at<int32_t>(c->lay.page_table), c->rt.max_pages_per_seq, c->at<int32_t>(c->lay.upd), nupd);
+        SV_HIP(c, hipGetLastError());
+    }
+    SV_HIP(c, hipEventRecord(c->staged[slot], c->stream));
+    c->staged_valid[slot] = true;
+    c->ring_pos = (slot + 1) % kRing;
+    return SV_OK;
+}
+
+static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int N, int K, int* splits_out) {
+    if (c->model.dtype == SV_BF16) {
+        const int s = pick_splits(M, N, K);
+        *splits_out = s;
+        SV_HIP(c, gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, c->gemm_variant, c->stream));
+    } else {
+        *splits_out = 1;
+        SV_HIP(c, gemm_f32((const float*)A, (const float*)W, out, M, N, K, c->stream));
+    }
+    return SV_OK;
+}
+
+// Rows are already described by batch_seq / last_tokens / drafts.  Leaves logits in the workspace.
+static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_tokens, const int32_t* drafts, int max_len_ub) {
+    const sv_model& m = c->model;
+    const Layout& L = c->lay;
+    const int T = B * n, d = m.d_model, qw = m.n_q_heads * m.head_dim, qkvw = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    hipStream_t st = c->stream;
+    float* h = c->at<float>(L.h);
+    float* part = c->at<float>(L.part);
+    void* a_norm = c->at<void>(L.a_norm);
+
+    RowPrep rp;
+    rp.batch_seq = c->at<int32_t>(L.batch_seq); rp.seq_len = c->at<int32_t>(L.seq_len);
+    rp.last_tokens = last_tokens; rp.drafts = drafts;
+    rp.row_tok = c->at<int32_t>(L.row_tok); rp.row_pos = c->at<int32_t>(L.row_pos); rp.row_slot = c->at<int32_t>(L.row_slot);
+    rp.rope = c->at<float>(L.rope);
+    rp.B = B; rp.n = n; rp.k = k; rp.head_dim = m.head_dim; rp.rope_theta = m.rope_theta;
+    SV_HIP(c, prep_rows(rp, st));
+    SV_HIP(c, embed_rows(c->embed, m.dtype, rp.row_tok, h, T, d, st));
+
+    int pending = 0;      // split-K partials of the previous projection, still to be added to h
+    for (int l = 0; l < m.n_layers; ++l) {
+        SV_HIP(c, add_rmsnorm(h, part, pending, c->ln1[l], a_norm, m.dtype, T, d, m.rms_eps, st));
+        int s_qkv = 1;
+        SV_TRY(gemm(c, a_norm, c->wqkv[l], part, T, qkvw, d, &s_qkv));
+        RopeAppend ra;
+        ra.qkv_part = part; ra.S = s_qkv; ra.rope = rp.rope; ra.row_slot = rp.row_slot; ra.batch_seq = rp.batch_seq;
+        ra.page_table = c->at<int32_t>(L.page_table); ra.max_pages_per_seq = c->rt.max_pages_per_seq;
+        ra.q_out = c->at<void>(L.q); ra.pool = c->rt.kv_pool; ra.geom = c->geom; ra.layer = l;
+        ra.T = T; ra.n = n; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.dtype = m.dtype;
+        SV_HIP(c, rope_append(ra, st));
+
+        AttnArgs aa;
+        aa.q = ra.q_out; aa.pool = c->rt.kv_pool; aa.geom = c->geom; aa.layer = l;
+        aa.page_table = ra.page_table; aa.max_pages_per_seq = c->rt.max_pages_per_seq;
+        aa.batch_seq = rp.batch_seq; aa.seq_len = rp.seq_len; aa.out = c->at<void>(L.attn);
+        aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml);
+        aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
+        aa.chunk_keys = kChunkKeys;
+        aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
+        aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + kChunkKeys - 1) / kChunkKeys);
+        SV_HIP(c, attention(aa, st));
+
+        int s_o = 1;
+        SV_TRY(gemm(c, aa.out, c->wo[l], part, T, d, qw, &s_o));
+        SV_HIP(c, add_rmsnorm(h, part, s_o, c->ln2[l], a_norm, m.dtype, T, d, m.rms_eps, st));
+        int s_gu = 1;
+        SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
+        SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, st));
+        SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
+    }
+    SV_HIP(c, add_rmsnorm(h, part, pending, c->final_norm, a_norm, m.dtype, T, d, m.rms_eps, st));
+    if (m.dtype == SV_BF16)
+        SV_HIP(c, gemm_bf16((const bf16_t*)a_norm, (const bf16_t*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, 1,
+                            c->gemm_variant, st));
+    else
+        SV_HIP(c, gemm_f32((const float*)a_norm, (const float*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, st));
+    return SV_OK;
+}
+
+extern "C" int verify_prefill(sv_ctx* c, int32_t id, const int32_t* tokens, int32_t n, float* last_logits) {
+    if (!c || !tokens) return SV_EINVAL;
+    if (n <= 0) return c->fail(SV_EINVAL, "prefill of %d tokens", n);
+    if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+    if (pages_for(c, c->seqs[id].len_ub + n) > c->rt.max_pages_per_seq)
+        return c->fail(SV_ENOPAGES, "sequence %d would exceed max_pages_per_seq", id);
+    const int chunk_max = std::min(c->lay.T, 64);
+    int done = 0;
+    while (done < n) {
+        const int cn = std::min(chunk_max, n - done);
+        SV_TRY(stage_batch(c, &id, 1, cn));
+        // a chunk is x0 plus one chain of cn-1 "drafts": causal visibility, every row kept
+        SV_TRY(forward_rows(c, 1, cn, cn - 1, tokens + done, tokens + done + 1, c->seqs[id].len_ub));
+        SV_HIP(c, add_len(c->at<int32_t>(c->lay.seq_len), c->at<int32_t>(c->lay.batch_seq), 1, cn, c->stream));
+        c->seqs[id].len_ub += cn;
+        done += cn;
+        if (done == n && last_logits)
+            SV_HIP(c, hipMemcpyAsync(last_logits, c->at<float>(c->lay.logits) + (size_t)(cn - 1) * c->model.vocab,
+                                     sizeof(float) * c->model.vocab, hipMemcpyDeviceToDevice, c->stream));
+    }
+    return SV_OK;
+}
+
+extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts, const float* draft_probs,
+                           const float* uniforms, const sv_out* out) {
+    if (!c || !bt || !out) return SV_EINVAL;
+    const int B = bt->B, k = bt->k, N = bt->N;
+    if (B <= 0 || B > c->rt.max_batch || k < 0 || k > c->rt.max_k || N <= 0 || N > c->rt.max_chains)
+        return c->fail(SV_EINVAL, "batch %d / k %d / chains %d outside the limits given at init", B, k, N);
+    if (!bt->seq_ids || !bt->last_tokens || (k > 0 && !drafts) || !out->accepted_len || !out->out_tokens || !out->best_chain)
+        return c->fail(SV_EINVAL, "null argument");
+    if (c->rt.verify_mode == SV_STOCHASTIC && !uniforms) return c->fail(SV_EINVAL, "stochastic verification needs uniforms");
+    const int n = 1 + N * k;
+    SV_TRY(stage_batch(c, bt->seq_ids, B, n));
+    int max_ub = 0;
+    for (int b = 0; b < B; ++b) max_ub = std::max(max_ub, c->seqs[bt->seq_ids[b]].len_ub);
+    SV_TRY(forward_rows(c, B, n, k, bt->last_tokens, drafts, max_ub));
+
+    const Layout& L = c->lay;
+    SampleArgs sa;
+    sa.logits = c->at<float>(L.logits); sa.drafts = drafts; sa.draft_probs = draft_probs; sa.uniforms = uniforms;
+    sa.draft_lens = bt->draft_lens; sa.row_stat = c->at<float>(L.row_stat);
+    sa.chain_acc = c->at<int32_t>(L.chain_acc); sa.chain_tok = c->at<int32_t>(L.chain_tok); sa.chain_row = c->at<int32_t>(L.chain_row);
+    sa.accepted_len = out->accepted_len; sa.out_tokens = out->out_tokens; sa.best_chain = out->best_chain;
+    sa.B = B; sa.N = N; sa.k = k; sa.V = c->model.vocab; sa.verify_mode = c->rt.verify_mode; sa.sample_mode = c->rt.sample_mode;
+    sa.temperature = c->rt.temperature;
+    SV_HIP(c, sample_verify(sa, c->stream));
+
+    RollbackArgs rb;
+    rb.pool = c->rt.kv_pool; rb.geom = c->geom; rb.n_layers = c->model.n_layers; rb.dtype = c->model.dtype;
+    rb.page_table = c->at<int32_t>(L.page_table); rb.max_pages_per_seq = c->rt.max_pages_per_seq;
+    rb.batch_seq = c->at<int32_t>(L.batch_seq); rb.seq_len = c->at<int32_t>(L.seq_len);
+    rb.accepted_len = out->accepted_len; rb.best_chain = out->best_chain; rb.B = B; rb.N = N; rb.k = k;
+    SV_HIP(c, rollback(rb, c->stream));
+    if (out->logits)
+        SV_HIP(c, hipMemcpyAsync(out->logits, sa.logits, sizeof(float) * (size_t)B * n * c->model.vocab,
+                                 hipMemcpyDeviceToDevice, c->stream));
+    for (int b = 0; b < B; ++b) c->seqs[bt->seq_ids[b]].len_ub += k + 1;
+    return SV_OK;
+}
+
+// -------------------------------------------------- single-operation entry points ---
+
+extern "C" int sv_op_gemm_bf16(const void* A, const void* W, float* out, int M, int N, int K, int splits, int variant,
+                               void* stream) {
+    if (!A || !W || !out || M <= 0 || !gemm_bf16_shape_ok(N, K, splits)) return SV_EINVAL;
+    return gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, splits, variant, (hipStream_t)stream) == hipSuccess
+               ? SV_OK : SV_EHIP;
+}
+
+extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const float* draft_probs, const float* uniforms,
+                            const int32_t* draft_lens, int B, int N, int k, int V, int verify_mode, int sample_mode,
+                            float temperature, void* scratch, int32_t* accepted_len, int32_t* out_tokens,
+                            int32_t* best_chain, void* stream) {
+    if (!logits || (k > 0 && !drafts) || !scratch || !accepted_len || !out_tokens || !best_chain || B <= 0 || N <= 0 ||
+        k < 0 || V <= 0 || !(temperature > 0.f) || (verify_mode == SV_STOCHASTIC && !uniforms))
+        return SV_EINVAL;
+    const int T = B * (1 + N * k), S = B * N;
+    char* p = reinterpret_cast<char*>(scratch);
+    SampleArgs sa;
+    sa.logits = logits; sa.drafts = drafts; sa.draft_probs = draft_probs; sa.uniforms = uniforms; sa.draft_lens = draft_lens;
+    sa.row_stat = reinterpret_cast<float*>(p); p += align_up(sizeof(float) * 4 * T);
+    sa.chain_acc = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * S);
+    sa.chain_tok = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * S);
+    sa.chain_row = reinterpret_cast<int32_t*>(p);
+    sa.accepted_len = accepted_len; sa.out_tokens = out_tokens; sa.best_chain = best_chain;
+    sa.B = B; sa.N = N; sa.k = k; sa.V = V; sa.verify_mode = verify_mode; sa.sample_mode = sample_mode; sa.temperature = temperature;
+    return sample_verify(sa, (hipStream_t)stream) == hipSuccess ? SV_OK : SV_EHIP;
+}
+
+extern "C" size_t sv_op_sample_scratch_bytes(int B, int N, int k) {
+    if (B <= 0 || N <= 0 || k < 0) return 0;
+    return align_up(sizeof(float) * 4 * (size_t)B * (1 + N * k)) + 3 * align_up(sizeof(int32_t) * (size_t)B * N);
+}
+
+extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, int k, int layer, const void* q, void* out) {
+    if (!c || !seq_ids || !q || !out) return SV_EINVAL;
+    if (B <= 0 || B > c->rt.max_batch || n <= 0 || B * n > c->lay.T || k < 0 || layer < 0 || layer >= c->model.n_layers ||
+        (k > 0 && (n - 1) % k != 0) || (k == 0 && n != 1))
+        return c->fail(SV_EINVAL, "attention of %d x %d rows (k=%d, layer %d) outside the limits given at init", B, n, k, layer);
+    SV_TRY(stage_batch(c, seq_ids, B, n));
+    int max_ub = 0;
+    for (int b = 0; b < B; ++b) max_ub = std::max(max_ub, c->seqs[seq_ids[b]].len_ub);
+    const sv_model& m = c->model;
+    AttnArgs aa;
+    aa.q = q; aa.pool = c->rt.kv_pool; aa.geom = c->geom; aa.layer = layer;
+    aa.page_table = c->at<int32_t>(c->lay.page_table); aa.max_pages_per_seq = c->rt.max_pages_per_seq;
+    aa.batch_seq = c->at<int32_t>(c->lay.batch_seq); aa.seq_len = c->at<int32_t>(c->lay.seq_len); aa.out = out;
+    aa.part_o = c->at<float>(c->lay.part_o); aa.part_ml = c->at<float>(c->lay.part_ml);
+    aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
+    aa.chunk_keys = kChunkKeys; aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
+    aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + kChunkKeys - 1) / kChunkKeys);
+    SV_HIP(c, attention(aa, c->stream));
+    return SV_OK;
+}
+
+extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
+    if (!c) return SV_EINVAL;
+    switch (option) {
+        case SV_OPT_GEMM_VARIANT:
+            if (value < 0 || value > 2) return c->fail(SV_EINVAL, "gemm variant %d", value);
+            c->gemm_variant = value;
+            return SV_OK;
+        case SV_OPT_ATTN_GENERIC:
+            c->attn_generic = value != 0;
+            return SV_OK;
+        case SV_OPT_ATTN_MIN_ROW_TILES:
+            if (value < 1 || value > 4) return c->fail(SV_EINVAL, "row tiles %d", value);
+            c->attn_min_rt = value;
+            return SV_OK;
+        default:
+            return c->fail(SV_EINVAL, "unknown option %d", option);
+    }
+}

@@ -1,0 +1,208 @@
+// The memory-bound glue of the forward pass: row preparation (positions, cache slots, rotary table),
+// embedding gather, residual-add + RMSNorm (which also sums split-K partial products), rotary embedding
+// + KV append into the paged cache, SwiGLU, and dense <-> paged KV copies.
+#include "common.h"
+#include "kernels.h"
+
+namespace sv {
+
+// One group per new row t = b*n + j.  Position = L + index-in-chain, cache slot = L + j.  The rotary
+// angle pos * theta^(-2i/hd) is formed in double: at positions of tens of thousands a float angle is
+// off by ~1e-3 rad, which is visible after rounding q and k to bf16.
+__global__ void prep_rows_kernel(RowPrep p) {
+    const int t = blockIdx.x, b = t / p.n, j = t % p.n;
+    const int L = p.seq_len[p.batch_seq[b]];
+    const int pos = L + row_index_in_chain(j, p.k);
+    if (threadIdx.x == 0) {
+        p.row_tok[t] = j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
+        p.row_pos[t] = pos;
+        p.row_slot[t] = L + j;
+    }
+    const int half = p.head_dim / 2;
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+        const double inv_freq = pow((double)p.rope_theta, -2.0 * (double)i / (double)p.head_dim);
+        double s, c;
+        sincos((double)pos * inv_freq, &s, &c);
+        p.rope[((int64_t)t * half + i) * 2 + 0] = (float)c;
+        p.rope[((int64_t)t * half + i) * 2 + 1] = (float)s;
+    }
+}
+
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restrict__ row_tok, float* __restrict__ h, int d) {
+    const int t = blockIdx.x;
+    const T* src = embed + (int64_t)row_tok[t] * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) h[(int64_t)t * d + i] = Store<T>::load(src + i);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int S,
+                                                          int64_t part_stride, const T* __restrict__ w,
+                                                          T* __restrict__ a, int d, float eps) {
+    __shared__ float red[4];
+    const int t = blockIdx.x;
+    float* hr = h + (int64_t)t * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float x = hr[i];
+        for (int s = 0; s < S; ++s) x += part[s * part_stride + (int64_t)t * d + i];
+        hr[i] = x;
+        ss = fmaf(x, x, ss);
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float r = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) Store<T>::store(a + (int64_t)t * d + i, hr[i] * r * Store<T>::load(w + i));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(RopeAppend p) {
+    const int t = blockIdx.x, b = t / p.n;
+    const int hd = p.hd, half = hd / 2;
+    const int ncol = (p.Hq + 2 * p.Hkv) * hd;
+    const int64_t stride = (int64_t)p.T * ncol;
+    const float* src = p.qkv_part + (int64_t)t * ncol;
+    const int slot = p.row_slot[t];
+    const int page = p.page_table[(int64_t)p.batch_seq[b] * p.max_pages_per_seq + slot / p.geom.page_size];
+    const int tok = slot % p.geom.page_size;
+    T* pool = reinterpret_cast<T*>(p.pool);
+    auto val = [&](int col) {
+        float x = 0.f;
+        for (int s = 0; s < p.S; ++s) x += src[s * stride + col];
+        return x;
+    };
+    // rotated heads: q heads then k heads, one (head, pair) per iteration
+    const int nrot = (p.Hq + p.Hkv) * half;
+    for (int e = threadIdx.x; e < nrot; e += 256) {
+        const int head = e / half, i = e % half;
+        const float c = p.rope[((int64_t)t * half + i) * 2], s = p.rope[((int64_t)t * half + i) * 2 + 1];
+        const float x1 = val(head * hd + i), x2 = val(head * hd + i + half);
+        const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
+        if (head < p.Hq) {
+            T* q = reinterpret_cast<T*>(p.q_out) + ((int64_t)t * p.Hq + head) * hd;
+            Store<T>::store(q + i, o1);
+            Store<T>::store(q + i + half, o2);
+        } else {
+            const int kh = head - p.Hq;
+            Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i), o1);
+            Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i + half), o2);
+        }
+    }
+    const int nv = p.Hkv * hd;
+    for (int e = threadIdx.x; e < nv; e += 256) {
+        const int kh = e / hd, i = e % hd;
+        Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i), val((p.Hq + p.Hkv) * hd + e));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ part, int S, int64_t stride,
+                                                     T* __restrict__ act, int F) {
+    const int t = blockIdx.y;
+    const int f = blockIdx.x * 256 + threadIdx.x;
+    if (f >= F) return;
+    const float* src = part + (int64_t)t * 2 * F;
+    float g = 0.f, u = 0.f;
+    for (int s = 0; s < S; ++s) {
+        g += src[s * stride + f];
+        u += src[s * stride + F + f];
+    }
+    const float y = g / (1.0f + expf(-g)) * u;
+    Store<T>::store(act + (int64_t)t * F + f, y);
+}
+
+template <typename T>
+__global__ void kv_copy_kernel(T* pool, KvGeom g, int layer, const int32_t* __restrict__ pages, int pos0, T* k, T* v,
+                               bool to_pool) {
+    const int i = blockIdx.x, pos = pos0 + i;
+    const int page = pages[pos / g.page_size], tok = pos % g.page_size;
+    const int per = g.n_kv_heads * g.head_dim;
+    for (int e = threadIdx.x; e < per; e += blockDim.x) {
+        const int h = e / g.head_dim, d = e % g.head_dim;
+        const int64_t ki = kv_k_index(g, layer, page, h, tok, d), vi = kv_v_index(g, layer, page, h, tok, d);
+        if (to_pool) {
+            pool[ki] = k[(int64_t)i * per + e];
+            pool[vi] = v[(int64_t)i * per + e];
+        } else {
+            k[(int64_t)i * per + e] = pool[ki];
+            v[(int64_t)i * per + e] = pool[vi];
+        }
+    }
+}
+
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+__global__ void add_len_kernel(int32_t* seq_len, const int32_t* batch_seq, int B, int delta) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) seq_len[batch_seq[b]] += delta;
+}
+
+// ---------------------------------------------------------------- launchers ---
+
+hipError_t prep_rows(const RowPrep& p, hipStream_t st) {
+    hipLaunchKernelGGL(prep_rows_kernel, dim3(p.B * p.n), dim3(64), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, float* h, int T, int d, hipStream_t st) {
+    if (dtype == 1)
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(T), dim3(256), 0, st, (const bf16_t*)embed, row_tok, h, d);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(T), dim3(256), 0, st, (const float*)embed, row_tok, h, d);
+    return hipGetLastError();
+}
+
+hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
+                       hipStream_t st) {
+    const int64_t stride = (int64_t)T * d;
+    if (dtype == 1)
+        hipLaunchKernelGGL(add_rmsnorm_kernel<bf16_t>, dim3(T), dim3(256), 0, st, h, part, S, stride,
+                           (const bf16_t*)w, (bf16_t*)a, d, eps);
+    else
+        hipLaunchKernelGGL(add_rmsnorm_kernel<float>, dim3(T), dim3(256), 0, st, h, part, S, stride, (const float*)w,
+                           (float*)a, d, eps);
+    return hipGetLastError();
+}
+
+hipError_t rope_append(const RopeAppend& p, hipStream_t st) {
+    if (p.dtype == 1)
+        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(p.T), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL(rope_append_kernel<float>, dim3(p.T), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t swiglu(const float* gu_part, int S, void* act, int dtype, int T, int F, hipStream_t st) {
+    const int64_t stride = (int64_t)T * 2 * F;
+    dim3 grid((F + 255) / 256, T);
+    if (dtype == 1)
+        hipLaunchKernelGGL(swiglu_kernel<bf16_t>, grid, dim3(256), 0, st, gu_part, S, stride, (bf16_t*)act, F);
+    else
+        hipLaunchKernelGGL(swiglu_kernel<float>, grid, dim3(256), 0, st, gu_part, S, stride, (float*)act, F);
+    return hipGetLastError();
+}
+
+hipError_t kv_copy(void* pool, const KvGeom& geom, int layer, const int32_t* page_table_row, int pos0, int n, void* k,
+                   void* v, int dtype, bool to_pool, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (dtype == 1)
+        hipLaunchKernelGGL(kv_copy_kernel<bf16_t>, dim3(n), dim3(256), 0, st, (bf16_t*)pool, geom, layer,
+                           page_table_row, pos0, (bf16_t*)k, (bf16_t*)v, to_pool);
+    else
+        hipLaunchKernelGGL(kv_copy_kernel<float>, dim3(n), dim3(256), 0, st, (float*)pool, geom, layer, page_table_row,
+                           pos0, (float*)k, (float*)v, to_pool);
+    return hipGetLastError();
+}
+
+hipError_t set_i32(int32_t* p, int32_t v, hipStream_t st) {
+    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, st, p, v);
+    return hipGetLastError();
+}
+
+hipError_t add_len(int32_t* seq_len, const int32_t* batch_seq, int B, int delta, hipStream_t st) {
+    hipLaunchKernelGGL(add_len_kernel, dim3((B + 63) / 64), dim3(64), 0, st, seq_len, batch_seq, B, delta);
+    return hipGetLastError();
+}
+
+}  // namespace sv

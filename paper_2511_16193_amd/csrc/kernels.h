@@ -1,0 +1,97 @@
+// Host-callable launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "common.h"
+
+namespace sv {
+
+// ---- gemm.hip ----
+int gemm_bf16_shape_ok(int N, int K, int splits);
+hipError_t gemm_bf16(const bf16_t* A, const bf16_t* W, float* out, int M, int N, int K, int splits, int variant,
+                     hipStream_t st);
+hipError_t gemm_f32(const float* A, const float* W, float* out, int M, int N, int K, hipStream_t st);
+
+// ---- elementwise.hip ----
+struct RowPrep {
+    const int32_t* batch_seq;   // [B] sequence id per request
+    const int32_t* seq_len;     // [max_seqs] live lengths
+    const int32_t* last_tokens; // [B]
+    const int32_t* drafts;      // [B, N*k] (may be null when k == 0)
+    int32_t* row_tok;           // [T]
+    int32_t* row_pos;           // [T]
+    int32_t* row_slot;          // [T]
+    float* rope;                // [T, head_dim/2, 2] cos, sin
+    int B, n, k, head_dim;
+    float rope_theta;
+};
+hipError_t prep_rows(const RowPrep& p, hipStream_t st);
+hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, float* h, int T, int d, hipStream_t st);
+// h[t,:] += sum_s part[s][t,:] (S may be 0), then a[t,:] = storage(h * rsqrt(mean(h^2)+eps) * w)
+hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
+                       hipStream_t st);
+struct RopeAppend {
+    const float* qkv_part; int S;       // [S][T][(Hq+2Hkv)*hd]
+    const float* rope;                  // [T][hd/2][2]
+    const int32_t* row_slot;            // [T]
+    const int32_t* batch_seq;           // [B]
+    const int32_t* page_table; int max_pages_per_seq;
+    void* q_out;                        // [T][Hq][hd] storage type
+    void* pool; KvGeom geom; int layer;
+    int T, n, Hq, Hkv, hd, dtype;
+};
+hipError_t rope_append(const RopeAppend& p, hipStream_t st);
+hipError_t swiglu(const float* gu_part, int S, void* act, int dtype, int T, int F, hipStream_t st);
+hipError_t kv_copy(void* pool, const KvGeom& geom, int layer, const int32_t* page_table_row, int pos0, int n,
+                   void* k, void* v, int dtype, bool to_pool, hipStream_t st);
+hipError_t set_i32(int32_t* p, int32_t v, hipStream_t st);
+hipError_t add_len(int32_t* seq_len, const int32_t* batch_seq, int B, int delta, hipStream_t st);
+
+// ---- attention.hip ----
+struct AttnArgs {
+    const void* q;                      // [T][Hq][hd] storage type
+    const void* pool; KvGeom geom; int layer;
+    const int32_t* page_table; int max_pages_per_seq;
+    const int32_t* batch_seq;           // [B]
+    const int32_t* seq_len;             // [max_seqs]
+    void* out;                          // [T][Hq*hd] storage type
+    float* part_o;                      // [B][Hkv][max_chunks][rows_pad][hd]
+    float* part_ml;                     // [B][Hkv][max_chunks][rows_pad][2]
+    int B, n, k, Hq, Hkv, hd, dtype;
+    int chunk_keys, max_chunks;
+    int min_row_tiles;                  // lower bound on the 16-row tiles of the bf16 kernel (tuning)
+    bool force_generic;                 // take the untuned one-wave-per-row path whatever the shape
+};
+int attn_rows_pad(int n, int group);        // padded query rows per (request, kv head); 0 = MFMA path not applicable
+hipError_t attention(const AttnArgs& a, hipStream_t st);
+
+// ---- sampler.hip ----
+struct SampleArgs {
+    const float* logits;                // [T][V]
+    const int32_t* drafts;              // [B][N][k]
+    const float* draft_probs;           // [B][N][k][V] or null
+    const float* uniforms;              // [B][N][k+1] or null (greedy)
+    const int32_t* draft_lens;          // [B] or null
+    float* row_stat;                    // [T][4]: max logit, sum exp((x-max)/temp), argmax id (as int bits), unused
+    int32_t* chain_acc;                 // [B][N]
+    int32_t* chain_tok;                 // [B][N]
+    int32_t* chain_row;                 // [B][N] scratch
+    int32_t* accepted_len;              // [B]
+    int32_t* out_tokens;                // [B][k+1]
+    int32_t* best_chain;                // [B]
+    int B, N, k, V, verify_mode, sample_mode;
+    float temperature;
+};
+hipError_t sample_verify(const SampleArgs& a, hipStream_t st);
+struct RollbackArgs {
+    void* pool; KvGeom geom; int n_layers, dtype;
+    const int32_t* page_table; int max_pages_per_seq;
+    const int32_t* batch_seq;
+    int32_t* seq_len;
+    const int32_t* accepted_len;
+    const int32_t* best_chain;
+    int B, N, k;
+};
+hipError_t rollback(const RollbackArgs& a, hipStream_t st);
+
+}  // namespace sv

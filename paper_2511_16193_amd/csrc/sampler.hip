@@ -1,0 +1,284 @@
+// Accept / reject over the target logits, the replacement or bonus draw, the choice of the chain to
+// keep, and the cache rollback.  Three passes over vocabulary-wide data, all bound by HBM:
+//   row_stats   every logits row once: max, sum exp((x - max)/temp), argmax (lowest id on ties)
+//   accept      per (request, chain), scalar: walk the drafts; p_i(d_i) from the row statistics and
+//               one gathered logit; u_i * q_i(d_i) < p_i(d_i); record the row the final draw uses
+//   draw        per (request, chain), one pass over that row (and the draft distribution's row when
+//               a draft was rejected): weights w = max(p - q, 0) or p; inverse-CDF or exponential race
+// then select (longest chain) and rollback (move the kept chain's K/V next to x0, advance lengths).
+#include <math.h>
+#include "common.h"
+#include "kernels.h"
+
+namespace sv {
+
+constexpr int NT = 1024;
+
+__global__ __launch_bounds__(NT) void row_stats_kernel(const float* __restrict__ logits, float* __restrict__ stat,
+                                                       int V, float inv_temp) {
+    const int t = blockIdx.x;
+    const float* row = logits + (int64_t)t * V;
+    float m = -INFINITY, s = 0.f;
+    int am = 0x7fffffff;
+    for (int v = threadIdx.x; v < V; v += NT) {
+        const float x = row[v];
+        if (x > m) {
+            s = s * expf((m - x) * inv_temp) + 1.0f;
+            m = x;
+            am = v;
+        } else if (x > -INFINITY) {
+            s += expf((x - m) * inv_temp);
+        }
+    }
+    __shared__ float sm[NT / 64], ss[NT / 64];
+    __shared__ int sa[NT / 64];
+    // wave merge, then group merge: (m, s, am) with ties on m resolved to the lower id
+    auto merge = [&](float& m1, float& s1, int& a1, float m2, float s2, int a2) {
+        const float mm = fmaxf(m1, m2);
+        const float f1 = m1 == -INFINITY ? 0.f : expf((m1 - mm) * inv_temp);
+        const float f2 = m2 == -INFINITY ? 0.f : expf((m2 - mm) * inv_temp);
+        s1 = s1 * f1 + s2 * f2;
+        if (m2 > m1 || (m2 == m1 && a2 < a1)) a1 = a2;
+        m1 = mm;
+    };
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+        const int a2 = __shfl_xor(am, o);
+        merge(m, s, am, m2, s2, a2);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        sm[threadIdx.x >> 6] = m;
+        ss[threadIdx.x >> 6] = s;
+        sa[threadIdx.x >> 6] = am;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < NT / 64; ++w) merge(m, s, am, sm[w], ss[w], sa[w]);
+        stat[t * 4 + 0] = m;
+        stat[t * 4 + 1] = s;
+        stat[t * 4 + 2] = __int_as_float(am);
+        stat[t * 4 + 3] = 0.f;
+    }
+}
+
+// Logits row that holds the target distribution of draft slot i (1-based) of chain c of request b.
+__device__ __forceinline__ int slot_row(int b, int c, int i, int n, int k) {
+    return b * n + (i == 1 ? 0 : 1 + c * k + (i - 2));
+}
+
+__global__ void accept_kernel(SampleArgs a) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= a.B * a.N) return;
+    const int b = s / a.N, c = s % a.N;
+    const int n = 1 + a.N * a.k;
+    const int klim = a.draft_lens ? min(a.draft_lens[b], a.k) : a.k;
+    const float inv_temp = 1.0f / a.temperature;
+    int acc = 0;
+    for (int i = 1; i <= klim; ++i) {
+        const int row = slot_row(b, c, i, n, a.k);
+        const int x = a.drafts[(int64_t)s * a.k + (i - 1)];
+        bool ok;
+        if (a.verify_mode == 0) {
+            ok = x == __float_as_int(a.row_stat[row * 4 + 2]);
+        } else {
+            const float m = a.row_stat[row * 4], sum = a.row_stat[row * 4 + 1];
+            const float p = expf((a.logits[(int64_t)row * a.V + x] - m) * inv_temp) / sum;
+            const float q = a.draft_probs ? a.draft_probs[((int64_t)s * a.k + (i - 1)) * a.V + x] : 1.0f;
+            ok = a.uniforms[(int64_t)s * (a.k + 1) + (i - 1)] * q < p;
+        }
+        if (!ok) break;
+        ++acc;
+    }
+    a.chain_acc[s] = acc;
+    const int row = slot_row(b, c, acc + 1, n, a.k);
+    a.chain_row[s] = row;
+    if (a.verify_mode == 0) a.chain_tok[s] = __float_as_int(a.row_stat[row * 4 + 2]);
+}
+
+__device__ __forceinline__ uint64_t splitmix_finalise(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Final draw of one (request, chain).  Stochastic mode only.
+__global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
+    const int s = blockIdx.x;
+    const int b = s / a.N;
+    const int klim = a.draft_lens ? min(a.draft_lens[b], a.k) : a.k;
+    const int acc = a.chain_acc[s];
+    const bool rejected = acc < klim;
+    const int row = a.chain_row[s];
+    const float* lrow = a.logits + (int64_t)row * a.V;
+    const float* qrow = (rejected && a.draft_probs) ? a.draft_probs + ((int64_t)s * a.k + acc) * a.V : nullptr;
+    const int xrej = rejected ? a.drafts[(int64_t)s * a.k + acc] : -1;
+    const float inv_temp = 1.0f / a.temperature;
+    const float m = a.row_stat[row * 4], sum = a.row_stat[row * 4 + 1];
+    const float log_sum = logf(sum);
+    const float u = a.uniforms[(int64_t)s * (a.k + 1) + a.k];
+    const int V = a.V;
+
+    auto prob = [&](int v) { return expf((lrow[v] - m) * inv_temp) / sum; };
+    auto resid = [&](int v, float p) {          // weight of id v in the residual distribution
+        if (!rejected) return p;
+        const float q = qrow ? qrow[v] : (v == xrej ? 1.0f : 0.0f);
+        return fmaxf(p - q, 0.0f);
+    };
+
+    if (a.sample_mode == 1) {
+        // exponential race: argmax_v ln w_v - ln e_v ; track the residual's winner and, for the case that
+        // the residual is identically zero, the winner under p as well.
+        const uint64_t key = ((uint64_t)(uint32_t)s << 32) | (uint64_t)__float_as_uint(u);
+        float best_r = -INFINITY, best_p = -INFINITY;
+        int arg_r = 0x7fffffff, arg_p = 0x7fffffff;
+        for (int v = threadIdx.x; v < V; v += NT) {
+            const uint64_t z = splitmix_finalise(key + (uint64_t)(v + 1) * 0x9E3779B97F4A7C15ull);
+            const float U = ((float)(uint32_t)(z >> 32) + 0.5f) * 2.3283064365386963e-10f;
+            const float ln_e = logf(-log1pf(-U));
+            const float lp = (lrow[v] - m) * inv_temp - log_sum;
+            const float sp = lp - ln_e;
+            if (sp > best_p) { best_p = sp; arg_p = v; }
+            if (rejected) {
+                const float w = resid(v, expf(lp));
+                if (w > 0.f) {
+                    const float sr = logf(w) - ln_e;
+                    if (sr > best_r) { best_r = sr; arg_r = v; }
+                }
+            }
+        }
+        __shared__ float sh_r[NT / 64], sh_p[NT / 64];
+        __shared__ int sh_ar[NT / 64], sh_ap[NT / 64];
+        auto take = [](float& bv, int& ba, float ov, int oa) {
+            if (ov > bv || (ov == bv && oa < ba)) { bv = ov; ba = oa; }
+        };
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            take(best_r, arg_r, __shfl_xor(best_r, o), __shfl_xor(arg_r, o));
+            take(best_p, arg_p, __shfl_xor(best_p, o), __shfl_xor(arg_p, o));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            sh_r[threadIdx.x >> 6] = best_r; sh_ar[threadIdx.x >> 6] = arg_r;
+            sh_p[threadIdx.x >> 6] = best_p; sh_ap[threadIdx.x >> 6] = arg_p;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < NT / 64; ++w) {
+                take(best_r, arg_r, sh_r[w], sh_ar[w]);
+                take(best_p, arg_p, sh_p[w], sh_ap[w]);
+            }
+            a.chain_tok[s] = (rejected && best_r > -INFINITY) ? arg_r : arg_p;
+        }
+        return;
+    }
+
+    // inverse CDF over ascending id.  Thread i owns the contiguous ids [i*seg, (i+1)*seg); sums in double.
+    const int seg = (V + NT - 1) / NT;
+    const int v0 = threadIdx.x * seg, v1 = min(V, v0 + seg);
+    __shared__ double seg_r[NT], seg_p[NT];
+    __shared__ int pick_seg, use_p;
+    __shared__ double target, before;
+    double sr = 0.0, spp = 0.0;
+    for (int v = v0; v < v1; ++v) {
+        const float p = prob(v);
+        spp += (double)p;
+        sr += (double)resid(v, p);
+    }
+    seg_r[threadIdx.x] = sr;
+    seg_p[threadIdx.x] = spp;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot_r = 0.0, tot_p = 0.0;
+        for (int i = 0; i < NT; ++i) { tot_r += seg_r[i]; tot_p += seg_p[i]; }
+        const int up = !(tot_r > 0.0);
+        const double* segs = up ? seg_p : seg_r;
+        const double tgt = (double)u * (up ? tot_p : tot_r);
+        double run = 0.0;
+        int pick = -1;
+        for (int i = 0; i < NT; ++i) {
+            if (run + segs[i] > tgt) { pick = i; break; }
+            run += segs[i];
+        }
+        if (pick < 0) {          // u * total reached the total through rounding: last segment with weight
+            run = 0.0;
+            for (int i = 0; i < NT; ++i) if (segs[i] > 0.0) pick = i;
+            for (int i = 0; i < pick; ++i) run += segs[i];
+        }
+        pick_seg = pick; use_p = up; target = tgt; before = run;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x == pick_seg) {
+        double run = before;
+        int tok = -1, last_pos = -1;
+        for (int v = v0; v < v1; ++v) {
+            const float p = prob(v);
+            const float w = use_p ? p : resid(v, p);
+            if (w > 0.f) last_pos = v;
+            run += (double)w;
+            if (run > target) { tok = v; break; }
+        }
+        a.chain_tok[s] = tok >= 0 ? tok : last_pos;
+    }
+}
+
+__global__ void select_kernel(SampleArgs a) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.B) return;
+    int best = 0, acc = a.chain_acc[b * a.N];
+    for (int c = 1; c < a.N; ++c)
+        if (a.chain_acc[b * a.N + c] > acc) { acc = a.chain_acc[b * a.N + c]; best = c; }
+    a.accepted_len[b] = acc;
+    a.best_chain[b] = best;
+    int32_t* out = a.out_tokens + (int64_t)b * (a.k + 1);
+    for (int i = 0; i < acc; ++i) out[i] = a.drafts[((int64_t)b * a.N + best) * a.k + i];
+    out[acc] = a.chain_tok[b * a.N + best];
+    for (int i = acc + 1; i <= a.k; ++i) out[i] = -1;
+}
+
+// Move the kept chain's accepted entries to slots L+1 .. L+a (chain 0 already sits there).
+template <typename T>
+__global__ void compact_kernel(RollbackArgs r) {
+    const int b = blockIdx.x, layer = blockIdx.y;
+    const int best = r.best_chain[b], acc = r.accepted_len[b];
+    if (best == 0 || acc == 0) return;
+    const int seq = r.batch_seq[b];
+    const int L = r.seq_len[seq];
+    const int32_t* pages = r.page_table + (int64_t)seq * r.max_pages_per_seq;
+    T* pool = reinterpret_cast<T*>(r.pool);
+    const int per = r.geom.n_kv_heads * r.geom.head_dim;
+    for (int e = threadIdx.x; e < acc * per; e += blockDim.x) {
+        const int i = e / per + 1, rem = e % per, h = rem / r.geom.head_dim, d = rem % r.geom.head_dim;
+        const int src = L + 1 + best * r.k + (i - 1), dst = L + i;
+        const int sp = pages[src / r.geom.page_size], st = src % r.geom.page_size;
+        const int dp = pages[dst / r.geom.page_size], dt = dst % r.geom.page_size;
+        pool[kv_k_index(r.geom, layer, dp, h, dt, d)] = pool[kv_k_index(r.geom, layer, sp, h, st, d)];
+        pool[kv_v_index(r.geom, layer, dp, h, dt, d)] = pool[kv_v_index(r.geom, layer, sp, h, st, d)];
+    }
+}
+
+__global__ void commit_len_kernel(RollbackArgs r) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < r.B) r.seq_len[r.batch_seq[b]] += r.accepted_len[b] + 1;
+}
+
+hipError_t sample_verify(const SampleArgs& a, hipStream_t st) {
+    const int T = a.B * (1 + a.N * a.k), S = a.B * a.N;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(T), dim3(NT), 0, st, a.logits, a.row_stat, a.V, 1.0f / a.temperature);
+    hipLaunchKernelGGL(accept_kernel, dim3((S + 63) / 64), dim3(64), 0, st, a);
+    if (a.verify_mode != 0) hipLaunchKernelGGL(draw_kernel, dim3(S), dim3(NT), 0, st, a);
+    hipLaunchKernelGGL(select_kernel, dim3((a.B + 63) / 64), dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t rollback(const RollbackArgs& r, hipStream_t st) {
+    if (r.N > 1) {
+        if (r.dtype == 1)
+            hipLaunchKernelGGL(compact_kernel<bf16_t>, dim3(r.B, r.n_layers), dim3(256), 0, st, r);
+        else
+            hipLaunchKernelGGL(compact_kernel<float>, dim3(r.B, r.n_layers), dim3(256), 0, st, r);
+    }
+    hipLaunchKernelGGL(commit_len_kernel, dim3((r.B + 63) / 64), dim3(64), 0, st, r);
+    return hipGetLastError();
+}
+
+}  // namespace sv

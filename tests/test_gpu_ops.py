@@ -1,0 +1,188 @@
+"""Device parity of single stages (through the C ABI) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import model as M
+from oracle import verify as OV
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bf16_cpu(shape, std, seed):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(shape, generator=g) * std).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("M_,N,K,splits", [(320, 512, 1024, 1), (37, 256, 512, 4), (129, 128, 64, 1), (1, 384, 2048, 8),
+                                           (700, 640, 448, 1)])
+def test_gemm_bf16_matches_float64_product(variant, M_, N, K, splits):
+    """Several tiles plus a ragged last row tile; every split count; the reduction in float64 on the
+    same bf16 inputs is the reference.  fp32 accumulation of K <= 2048 products of magnitude ~0.02:
+    absolute error far below 1e-4."""
+    from paper_2511_16193_amd import op_gemm_bf16
+    if K % (64 * splits):
+        pytest.skip("K not divisible")
+    a = bf16_cpu((M_, K), 1.0, 1)
+    w = bf16_cpu((N, K), 0.02, 2)
+    want = M.matmul_wt(a.float().numpy().astype(np.float64), w.float().numpy())
+    got = op_gemm_bf16(a.to(DEV), w.to(DEV), splits=splits, variant=variant)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64).sum(axis=0)
+    assert np.max(np.abs(got - want)) < 1e-4
+
+
+@pytest.mark.parametrize("k,n_chains,group", [(0, 1, 7), (1, 1, 7), (2, 1, 7), (4, 1, 7), (8, 1, 7), (4, 1, 8), (3, 3, 4),
+                                              (8, 3, 5)])
+def test_attention_bf16_matches_oracle(k, n_chains, group):
+    """Verify attention alone: n = 1 + N*k rows per request over a paged bf16 cache, with the head
+    grouping of the benchmark shapes (7, 8, 5 q heads per kv head) and lengths that put the new rows
+    at the start, in the middle and at the end of a 32-key tile, of a page and of a 1024-key chunk,
+    plus empty and multi-chunk caches.  The output is rounded to bf16 (half a unit in the last place) and the
+    MFMA path also rounds the softmax weights to bf16 before the PV product (up to another unit when a row has
+    only a few keys, relative to the weighted mean of |v|): |got - want| <= 2^-8 (|want| + sum_j p_j |v_j|)."""
+    import paper_2511_16193_amd as P
+    hkv, hd = 2, 128
+    hq = hkv * group
+    n = 1 + n_chains * k
+    lengths = [0, 1, 31, 32, 63, 64, 1023, 1024, 1029, 2047, 3100]
+    B = len(lengths)
+    model = dict(n_layers=1, d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, d_ff=512, vocab=2048,
+                 dtype="bf16", rope_theta=1e6, rms_eps=1e-6)
+    wd = W.make_weights(W.Shape("attn", 1, 256, hq, hkv, hd, 512, 2048), DEV)
+    ver = P.Verifier(model, wd, max_batch=B, max_k=max(k, 1), max_chains=n_chains, max_seqs=B, page_size=64,
+                     num_pages=B * 52, max_pages_per_seq=51, verify_mode=0)
+    q = bf16_cpu((B * n, hq, hd), 1.0, 3)
+    ks, vs = [], []
+    for b, L in enumerate(lengths):
+        ver.seq_add(b, L)
+        ks.append(bf16_cpu((L + n, hkv, hd), 1.0, 10 + b))
+        vs.append(bf16_cpu((L + n, hkv, hd), 1.0, 50 + b))
+    ids = list(range(B))
+    ver.op_attention(ids, n, k, 0, q.to(DEV))          # reserves the pages of the new rows
+    for b in range(B):
+        ver.kv_write(b, 0, 0, ks[b].to(DEV), vs[b].to(DEV))
+    _, _, vis = OV.new_token_layout(k, n_chains)
+    for generic in (0, 1):
+        ver.set_option(P.SV_OPT_ATTN_GENERIC, generic)
+        got = ver.op_attention(ids, n, k, 0, q.to(DEV))
+        torch.cuda.synchronize()
+        got = got.float().cpu().numpy().reshape(B, n, hq, hd)
+        for b, L in enumerate(lengths):
+            mask = np.concatenate([np.ones((n, L), dtype=bool), vis], axis=1)
+            want = M.attend(q[b * n:(b + 1) * n].double().numpy(), ks[b].double().numpy(), vs[b].double().numpy(), mask)
+            spread = M.attend(q[b * n:(b + 1) * n].double().numpy(), ks[b].double().numpy(),
+                              np.abs(vs[b].double().numpy()), mask)
+            tol = 2.0 ** -8 * (np.abs(want) + spread) + 1e-6
+            assert np.all(np.abs(got[b] - want) <= tol), (generic, b, L, float(np.max(np.abs(got[b] - want))))
+    ver.close()
+
+
+def random_case(B, N, k, V, seed, sigma_q=1.0, with_q=True):
+    rng = np.random.default_rng(seed)
+    logits = (rng.standard_normal((B, 1 + N * k, V)) * 1.2).astype(np.float32)
+    q = W.make_random_q((B, N, k), V, sigma_q, seed) if with_q and k else None
+    if k:
+        drafts = (W.sample_from(q, seed).numpy() if q is not None else rng.integers(0, V, (B, N, k))).astype(np.int64)
+        # make a good share of drafts likely: copy the target's argmax into some slots
+        per_chain = np.empty((B, N, k), dtype=np.int64)
+        for c in range(N):
+            rows = np.concatenate([logits[:, :1], logits[:, 1 + c * k: 1 + (c + 1) * k]], axis=1)[:, :k]
+            per_chain[:, c] = np.argmax(rows, axis=-1)
+        take = rng.random((B, N, k)) < 0.3
+        drafts = np.where(take, per_chain, drafts)
+    else:
+        drafts = np.zeros((B, N, 0), dtype=np.int64)
+    u = W.make_uniforms((B, N, k + 1), seed)
+    return logits, drafts, q, u
+
+
+def oracle_sample(logits, drafts, q, u, verify_mode, sample_mode, temperature, draft_lens=None):
+    B, N, k = drafts.shape
+    V = logits.shape[-1]
+    per_chain = np.empty((B, N, k + 1, V))
+    for c in range(N):
+        per_chain[:, c, 0] = logits[:, 0]
+        per_chain[:, c, 1:] = logits[:, 1 + c * k: 1 + (c + 1) * k]
+    S = B * N
+    lens = None if draft_lens is None else np.repeat(draft_lens, N)
+    if verify_mode == OV.GREEDY:
+        v = OV.verify_greedy(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k), lens)
+    else:
+        v = OV.verify_stochastic(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
+                                 None if q is None else q.numpy().reshape(S, k, V), u.reshape(S, k + 1),
+                                 np.arange(S, dtype=np.uint64), temperature, sample_mode, lens)
+    a = v.accepted.reshape(B, N)
+    best = np.argmax(a, axis=1)
+    out = np.full((B, k + 1), -1, dtype=np.int64)
+    for b in range(B):
+        ab = a[b, best[b]]
+        out[b, :ab] = drafts[b, best[b], :ab]
+        out[b, ab] = v.token.reshape(B, N)[b, best[b]]
+    margin = np.minimum(v.accept_margin, v.draw_margin).reshape(B, N).min(axis=1)
+    return a[np.arange(B), best], out, best, margin
+
+
+CASES = [
+    # B, N, k, V, verify_mode, sample_mode, temperature, with_q, ragged
+    (7, 1, 4, 2048, OV.GREEDY, 0, 1.0, False, False),
+    (9, 1, 4, 2048, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, 1.0, True, False),
+    (9, 1, 4, 2048, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, True, False),
+    (5, 3, 8, 4099, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 0.7, True, False),
+    (5, 3, 8, 4099, OV.GREEDY, 0, 1.0, False, True),
+    (6, 1, 4, 3001, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, False, False),       # one-hot drafts
+    (6, 1, 4, 3001, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, 1.3, False, True),
+    (4, 1, 0, 2048, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, False, False),       # k = 0: plain decoding
+    (16, 1, 4, 152064, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, True, False),     # full vocabulary
+    (8, 1, 4, 152064, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, 1.0, True, False),
+    (1, 1, 1, 16, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, 1.0, True, False),       # degenerate sizes
+]
+
+
+@pytest.mark.parametrize("B,N,k,V,vmode,smode,temp,with_q,ragged", CASES)
+def test_sampler_matches_oracle_on_given_logits(B, N, k, V, vmode, smode, temp, with_q, ragged):
+    """Identical fp32 logits on both sides: accepted lengths, kept chain and tokens must be identical
+    except where the oracle's own decision margin is below 1e-5 (fp32 vs fp64 evaluation of exp/log)."""
+    from paper_2511_16193_amd import op_sample
+    logits, drafts, q, u = random_case(B, N, k, V, 100 + B + k + V % 7, with_q=with_q)
+    lens = np.random.default_rng(5).integers(0, k + 1, B) if ragged else None
+    a, out, best, margin = oracle_sample(logits, drafts, q, u, vmode, smode, temp, lens)
+    ga, gout, gbest = op_sample(
+        torch.from_numpy(logits).to(DEV), torch.from_numpy(drafts).to(torch.int32).to(DEV).contiguous(),
+        None if q is None else q.to(DEV).contiguous(), torch.from_numpy(u).to(DEV),
+        verify_mode=vmode, sample_mode=smode, temperature=temp,
+        draft_lens=None if lens is None else torch.from_numpy(lens).to(torch.int32).to(DEV))
+    torch.cuda.synchronize()
+    ga, gout, gbest = ga.cpu().numpy(), gout.cpu().numpy(), gbest.cpu().numpy()
+    bad = [b for b in range(B) if not (ga[b] == a[b] and gbest[b] == best[b] and np.array_equal(gout[b], out[b]))]
+    for b in bad:
+        assert margin[b] < 1e-5, (b, ga[b], a[b], gout[b], out[b], margin[b])
+    assert len(bad) <= max(1, B // 8)
+    assert a.max() > 0 or k == 0 or not with_q or ragged
+
+
+def test_sampler_zero_residual_falls_back_to_target():
+    """p and q one-hot on the same token (all other logits -inf) and a draft elsewhere: p(x) = q(x) = 0, so
+    u*q(x) < p(x) fails and the draft is rejected, yet max(p - q, 0) is identically zero: the draw must fall
+    back to p."""
+    from paper_2511_16193_amd import op_sample
+    V = 64
+    logits = np.full((1, 2, V), -np.inf, dtype=np.float32)
+    logits[0, 0, 7] = 20.0                          # p = one-hot(7) to fp32 precision
+    logits[0, 1, 9] = 20.0
+    q = np.zeros((1, 1, 1, V), dtype=np.float32)
+    q[0, 0, 0, 7] = 1.0                             # q = one-hot(7): p - q == 0 everywhere
+    drafts = np.array([[[3]]])                      # the draft itself is a token with p = q = 0 -> rejected (u*0 < 0 false)
+    u = np.array([[[0.5, 0.25]]], dtype=np.float32)
+    for smode in (OV.SAMPLE_INVERSE_CDF, OV.SAMPLE_EXP_RACE):
+        v = OV.verify_stochastic(logits.astype(np.float64), drafts.reshape(1, 1), q.reshape(1, 1, V), u.reshape(1, 2),
+                                 np.zeros(1, np.uint64), 1.0, smode)
+        assert v.accepted[0] == 0 and v.zero_residual[0] and v.token[0] == 7
+        ga, gout, _ = op_sample(torch.from_numpy(logits).to(DEV), torch.from_numpy(drafts).to(torch.int32).to(DEV),
+                                torch.from_numpy(q).to(DEV), torch.from_numpy(u).to(DEV),
+                                verify_mode=OV.STOCHASTIC, sample_mode=smode)
+        torch.cuda.synchronize()
+        assert int(ga[0]) == 0 and int(gout[0, 0]) == 7
