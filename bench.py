@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched speculative-verification step on one MI355X.
+
+One "step" = one whole verification pass over a batch of synthetic requests:
+forward of the target over the k drafts (+ x0) of every request against its
+paged KV cache, accept/reject + replacement/bonus draw, chain choice, rollback.
+The cache is put back to the same saved lengths before every step, so every
+step verifies the same drafts against the same state.
+
+Prints ONE JSON line: accepted tokens/s (tokens emitted per verification, the
+supplied token included, summed over the batch, per second of step time), the
+roofline figures of the kernel class that takes most of the step, and the CPU
+oracle timed on a small sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def gemm_flops_per_step(s, T):
+    qw, kvw = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    per_layer = s.d_model * (qw + 2 * kvw) + qw * s.d_model + 3 * s.d_model * s.d_ff
+    return 2.0 * T * (s.n_layers * per_layer + s.vocab * s.d_model), 4 * s.n_layers + 1
+
+
+def attention_bytes_per_layer(s, lengths, n):
+    kv_row = 2 * s.n_kv_heads * s.head_dim * 2                      # K and V of one token in one layer, bf16
+    q_o = 2 * len(lengths) * n * s.n_q_heads * s.head_dim * 2       # Q read + output written
+    return float(sum(int(L) + n for L in lengths)) * kv_row + q_o
+
+
+def cpu_baseline(case, n_seqs):
+    """Time the oracle, as it stands, on the first n_seqs requests of the same workload."""
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle import model as M, verify as OV
+    import workloads as W
+    s = case.shape
+    spec = M.ModelSpec(**s.model_fields())
+    log(f"cpu baseline: staging weights and the cache of {n_seqs} requests on the host ...")
+    wn = W.weights_to_numpy(case.weights)
+    n = 1 + case.N * case.k
+    caches = []
+    for b in range(n_seqs):
+        L = int(case.lengths[b])
+        c = M.SeqCache(spec, L + n + 1)
+        for l in range(s.n_layers):
+            k, v = case.kv_block(b, l)
+            c.k[l][:L] = k.float().cpu().numpy()
+            c.v[l][:L] = v.float().cpu().numpy()
+        c.length = L
+        caches.append(c)
+    x0 = case.x0[:n_seqs].cpu().numpy().astype(np.int64)
+    drafts = case.drafts[:n_seqs].cpu().numpy().astype(np.int64)
+    q = case.draft_probs[:n_seqs].cpu().numpy()
+    u = case.uniforms[:n_seqs].cpu().numpy()
+    log("cpu baseline: running the oracle ...")
+    t0 = time.perf_counter()
+    r = OV.verify_step(spec, wn, caches, x0, drafts, q, u, verify_mode=OV.STOCHASTIC,
+                       sample_mode=OV.SAMPLE_EXP_RACE, temperature=1.0)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    emitted = int((r.accepted_len + 1).sum())
+    log(f"cpu baseline: {emitted} tokens in {dt:.1f} s on {threads} threads")
+    return {"value": emitted / dt, "unit": "accepted tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {n_seqs} of {case.B} requests of {s.name}, one step, {dt:.1f} s; weights and cache "
+                      f"staged on the host beforehand (not timed)"}, r
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--sigma", type=float, default=None)
+    ap.add_argument("--cpu-seqs", type=int, default=2, help="requests in the oracle sample (0 = skip)")
+    ap.add_argument("--gemm-variant", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the verification step on ONE GPU (requests shard across workers "
+              "with no exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as W
+    from workloads.device_case import DeviceCase
+    import paper_2511_16193_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        sys.exit(1)
+    shape = W.CONFIGS[args.config]
+    case = DeviceCase(shape, k=args.k, log=log)
+    if args.gemm_variant is not None:
+        case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
+    log("drafting (noisy-target drafts through plain decoding steps) ...")
+    case.noisy_target_drafts(None if args.sigma is None else [args.sigma])
+    B, N, k = case.B, case.N, case.k
+    n = 1 + N * k
+    T = B * n
+    out = {"accepted_len": torch.empty(B, dtype=torch.int32, device=case.device),
+           "out_tokens": torch.empty((B, k + 1), dtype=torch.int32, device=case.device),
+           "best_chain": torch.empty(B, dtype=torch.int32, device=case.device)}
+
+    def run(steps):
+        for _ in range(steps):
+            case.reset()
+            case.step(out=out)
+
+    log(f"warm-up {args.warmup} steps ...")
+    run(args.warmup)
+    torch.cuda.synchronize()
+    # un-instrumented pass, for reference in the log
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the timed region: K steps, with the event brackets of the kernel kinds that carry the roofline
+    case.ver.profile_enable((1 << P.SV_PROF_GEMM) | (1 << P.SV_PROF_ATTENTION) | (1 << P.SV_PROF_SAMPLER))
+    run(1)
+    for kind in (P.SV_PROF_GEMM, P.SV_PROF_ATTENTION, P.SV_PROF_SAMPLER):
+        case.ver.profile_read(kind)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    gemm_ms, gemm_n = case.ver.profile_read(P.SV_PROF_GEMM)
+    attn_ms, attn_n = case.ver.profile_read(P.SV_PROF_ATTENTION)
+    samp_ms, samp_n = case.ver.profile_read(P.SV_PROF_SAMPLER)
+    case.ver.profile_enable(0)
+    log(f"step {ms_per_step:.3f} ms with event brackets ({plain_ms:.3f} ms without); per step: gemm "
+        f"{gemm_ms / args.steps:.3f} ms / {gemm_n // args.steps} launches, attention {attn_ms / args.steps:.3f} ms / "
+        f"{attn_n // args.steps}, sampler {samp_ms / args.steps:.3f} ms")
+
+    acc = out["accepted_len"].cpu().numpy()
+    emitted = int((acc + 1).sum())
+    flops, gemm_launches = gemm_flops_per_step(shape, T)
+    abytes = attention_bytes_per_layer(shape, case.lengths, n)
+    gemm_tflops = flops / gemm_launches / (gemm_ms / gemm_n * 1e-3) / 1e12
+    attn_gbs = abytes / (attn_ms / attn_n * 1e-3) / 1e9
+    roof_gemm = {"kernel": "gemm_bf16_kernel (all projections + LM head)", "bound": "mfma", "achieved": gemm_tflops,
+                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                 "avg_launch_ms": gemm_ms / gemm_n, "launches_per_step": gemm_n // args.steps}
+    roof_attn = {"kernel": "attn_bf16_kernel + attn_merge_kernel (one layer)", "bound": "hbm", "achieved": attn_gbs,
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": attn_gbs / PEAK_HBM_GBS, "traffic": None,
+                 "avg_launch_ms": attn_ms / attn_n, "launches_per_step": attn_n // args.steps}
+    dominant, other = (roof_gemm, roof_attn) if gemm_ms >= attn_ms else (roof_attn, roof_gemm)
+
+    cpu = None
+    if args.cpu_seqs > 0:
+        cpu, _ = cpu_baseline(case, min(args.cpu_seqs, B))
+
+    res = {
+        "metric": "accepted tokens/s of batched spec-verify step", "value": emitted / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": shape.name, "batch": B, "k": k, "chains": N, "rows_per_step": T,
+                   "prefix_tokens": int(case.lengths.sum()), "draft_sigma": list(shape.draft_sigma) if args.sigma is None else [args.sigma],
+                   "verify": "stochastic, exponential-race draw, temperature 1.0"},
+        "accepted_drafts_per_step": int(acc.sum()), "emitted_tokens_per_step": emitted,
+        "accepted_drafts_tokens_per_s": int(acc.sum()) / (ms_per_step * 1e-3),
+        "roofline": dominant, "roofline_other": [other],
+        "sampler_ms_per_step": samp_ms / args.steps, "ms_per_step_without_event_brackets": plain_ms,
+        "cpu_baseline": cpu,
+    }
+    case.close()
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

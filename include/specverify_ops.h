@@ -43,6 +43,18 @@ int sv_op_sample(const float *logits, const int32_t *drafts, const float *draft_
  * type).  n = 1 + N*k.  Lengths are not changed. */
 int sv_op_attention(sv_ctx *, const int32_t *seq_ids, int B, int n, int k, int layer, const void *q, void *out);
 
+/* Set the live lengths of n sequences at once (HOST arrays; same meaning as verify_seq_set_len, one
+ * small copy and one launch instead of n).  Used to put a batch back to a saved state between steps. */
+int sv_seq_set_lens(sv_ctx *, const int32_t *seq_ids, const int32_t *lens, int n);
+
+/* Per-kind kernel timing inside verify_step / verify_prefill.  While bit k of kind_mask is set, every
+ * launch group of kind k is bracketed by a pair of HIP events on the context's stream.
+ * sv_profile_read synchronises the stream, returns the summed elapsed time and the number of
+ * bracketed groups of that kind since the last read, and forgets them. */
+enum { SV_PROF_GEMM = 0, SV_PROF_ATTENTION = 1, SV_PROF_SAMPLER = 2, SV_PROF_ROLLBACK = 3, SV_PROF_KINDS = 4 };
+int sv_profile_enable(sv_ctx *, unsigned kind_mask);
+int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launches /* host */);
+
 /* Tuning / diagnostic knobs of a context.
  *   SV_OPT_GEMM_VARIANT  work-group tile of the bf16 projections (0..2, default 0)
  *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)

@@ -19,12 +19,14 @@ SV_FP32, SV_BF16 = 0, 1
 SV_GREEDY, SV_STOCHASTIC = 0, 1
 SV_INVERSE_CDF, SV_EXP_RACE = 0, 1
 SV_OPT_GEMM_VARIANT, SV_OPT_ATTN_GENERIC, SV_OPT_ATTN_MIN_ROW_TILES = 1, 2, 3
+SV_PROF_GEMM, SV_PROF_ATTENTION, SV_PROF_SAMPLER, SV_PROF_ROLLBACK = 0, 1, 2, 3
 
 EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_step",
-    "sv_op_gemm_bf16", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_attention", "sv_set_option",
+    "sv_op_gemm_bf16", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
+    "sv_profile_read",
 ]
 
 
@@ -86,6 +88,9 @@ def load_library() -> C.CDLL:
     lib.sv_op_sample.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 5
     lib.sv_op_attention.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p]
+    lib.sv_seq_set_lens.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
+    lib.sv_profile_enable.argtypes = [C.c_void_p, C.c_uint]
+    lib.sv_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.sv_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
     return lib
 
@@ -254,6 +259,21 @@ class Verifier:
         ids = (C.c_int32 * B)(*[int(s) for s in seq_ids])
         self._check(self.lib.sv_op_attention(self.ctx, ids, B, n, k, layer, _ptr(q), _ptr(out)))
         return out
+
+    def seq_set_lens(self, seq_ids, lens):
+        n = len(seq_ids)
+        ids = (C.c_int32 * n)(*[int(s) for s in seq_ids])
+        ln = (C.c_int32 * n)(*[int(x) for x in lens])
+        self._check(self.lib.sv_seq_set_lens(self.ctx, ids, ln, n))
+
+    def profile_enable(self, kind_mask: int):
+        self._check(self.lib.sv_profile_enable(self.ctx, kind_mask))
+
+    def profile_read(self, kind: int):
+        """-> (total milliseconds, number of timed launch groups) since the last read; synchronises."""
+        ms, n = C.c_double(), C.c_int()
+        self._check(self.lib.sv_profile_read(self.ctx, kind, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def set_option(self, option: int, value: int):
         self._check(self.lib.sv_set_option(self.ctx, option, value))

@@ -101,6 +101,11 @@ __global__ void apply_page_updates_kernel(int32_t* page_table, int mpps, const i
     if (i < n) page_table[(int64_t)upd[3 * i] * mpps + upd[3 * i + 1]] = upd[3 * i + 2];
 }
 
+__global__ void set_lens_kernel(int32_t* seq_len, const int32_t* pairs, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) seq_len[pairs[2 * i]] = pairs[2 * i + 1];
+}
+
 }  // namespace
 
 struct sv_ctx {
@@ -121,6 +126,10 @@ struct sv_ctx {
     int gemm_variant;
     bool attn_generic;
     int attn_min_rt;
+    unsigned prof_mask;                                   // kinds of kernels to time with events
+    struct ProfRec { int kind; hipEvent_t a, b; };
+    std::vector<ProfRec> prof_recs;                       // recorded, not yet read
+    std::vector<hipEvent_t> prof_free;                    // event pool
     std::string err;
 
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -136,6 +145,29 @@ struct sv_ctx {
     int hip(hipError_t e, const char* what) {
         if (e == hipSuccess) return SV_OK;
         return fail(SV_EHIP, "%s: %s", what, hipGetErrorString(e));
+    }
+};
+
+// Brackets the launches of one kind with a pair of events on the context's stream when that kind is
+// being profiled.
+struct ProfScope {
+    sv_ctx* c; int kind; bool on; hipEvent_t a;
+    ProfScope(sv_ctx* c_, int kind_) : c(c_), kind(kind_), on(((c_->prof_mask >> kind_) & 1u) != 0), a(nullptr) {
+        if (!on) return;
+        a = take();
+        if (a) (void)hipEventRecord(a, c->stream); else on = false;
+    }
+    ~ProfScope() {
+        if (!on) return;
+        hipEvent_t b = take();
+        if (!b) { c->prof_free.push_back(a); return; }
+        (void)hipEventRecord(b, c->stream);
+        c->prof_recs.push_back({kind, a, b});
+    }
+    hipEvent_t take() {
+        if (!c->prof_free.empty()) { hipEvent_t e = c->prof_free.back(); c->prof_free.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        return hipEventCreate(&e) == hipSuccess ? e : nullptr;
     }
 };
 
@@ -213,6 +245,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->gemm_variant = 0;
     c->attn_generic = false;
     c->attn_min_rt = 1;
+    c->prof_mask = 0;
     const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8) + 8;
     for (int i = 0; i < kRing; ++i) { c->staging[i] = nullptr; c->staged[i] = nullptr; c->staged_valid[i] = false; }
     for (int i = 0; i < kRing; ++i) {
@@ -236,6 +269,8 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
 extern "C" void verify_destroy(sv_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
+    for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
     for (int i = 0; i < kRing; ++i) {
         if (c->staging[i]) (void)hipHostFree(c->staging[i]);
         if (c->staged[i]) (void)hipEventDestroy(c->staged[i]);
@@ -374,6 +409,7 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
 }
 
 static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int N, int K, int* splits_out) {
+    ProfScope prof(c, SV_PROF_GEMM);
     if (c->model.dtype == SV_BF16) {
         const int s = pick_splits(M, N, K);
         *splits_out = s;
@@ -425,7 +461,10 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.chunk_keys = kChunkKeys;
         aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
         aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + kChunkKeys - 1) / kChunkKeys);
-        SV_HIP(c, attention(aa, st));
+        {
+            ProfScope prof(c, SV_PROF_ATTENTION);
+            SV_HIP(c, attention(aa, st));
+        }
 
         int s_o = 1;
         SV_TRY(gemm(c, aa.out, c->wo[l], part, T, d, qw, &s_o));
@@ -436,11 +475,14 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
     }
     SV_HIP(c, add_rmsnorm(h, part, pending, c->final_norm, a_norm, m.dtype, T, d, m.rms_eps, st));
-    if (m.dtype == SV_BF16)
-        SV_HIP(c, gemm_bf16((const bf16_t*)a_norm, (const bf16_t*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, 1,
-                            c->gemm_variant, st));
-    else
-        SV_HIP(c, gemm_f32((const float*)a_norm, (const float*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, st));
+    {
+        ProfScope prof(c, SV_PROF_GEMM);
+        if (m.dtype == SV_BF16)
+            SV_HIP(c, gemm_bf16((const bf16_t*)a_norm, (const bf16_t*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, 1,
+                                c->gemm_variant, st));
+        else
+            SV_HIP(c, gemm_f32((const float*)a_norm, (const float*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, st));
+    }
     return SV_OK;
 }
 
@@ -490,14 +532,20 @@ extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts,
     sa.accepted_len = out->accepted_len; sa.out_tokens = out->out_tokens; sa.best_chain = out->best_chain;
     sa.B = B; sa.N = N; sa.k = k; sa.V = c->model.vocab; sa.verify_mode = c->rt.verify_mode; sa.sample_mode = c->rt.sample_mode;
     sa.temperature = c->rt.temperature;
-    SV_HIP(c, sample_verify(sa, c->stream));
+    {
+        ProfScope prof(c, SV_PROF_SAMPLER);
+        SV_HIP(c, sample_verify(sa, c->stream));
+    }
 
     RollbackArgs rb;
     rb.pool = c->rt.kv_pool; rb.geom = c->geom; rb.n_layers = c->model.n_layers; rb.dtype = c->model.dtype;
     rb.page_table = c->at<int32_t>(L.page_table); rb.max_pages_per_seq = c->rt.max_pages_per_seq;
     rb.batch_seq = c->at<int32_t>(L.batch_seq); rb.seq_len = c->at<int32_t>(L.seq_len);
     rb.accepted_len = out->accepted_len; rb.best_chain = out->best_chain; rb.B = B; rb.N = N; rb.k = k;
-    SV_HIP(c, rollback(rb, c->stream));
+    {
+        ProfScope prof(c, SV_PROF_ROLLBACK);
+        SV_HIP(c, rollback(rb, c->stream));
+    }
     if (out->logits)
         SV_HIP(c, hipMemcpyAsync(out->logits, sa.logits, sizeof(float) * (size_t)B * n * c->model.vocab,
                                  hipMemcpyDeviceToDevice, c->stream));
@@ -557,6 +605,54 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.chunk_keys = kChunkKeys; aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + kChunkKeys - 1) / kChunkKeys);
     SV_HIP(c, attention(aa, c->stream));
+    return SV_OK;
+}
+
+extern "C" int sv_profile_enable(sv_ctx* c, unsigned kind_mask) {
+    if (!c) return SV_EINVAL;
+    c->prof_mask = kind_mask & ((1u << SV_PROF_KINDS) - 1u);
+    return SV_OK;
+}
+
+extern "C" int sv_profile_read(sv_ctx* c, int kind, double* total_ms, int* launches) {
+    if (!c || !total_ms || !launches || kind < 0 || kind >= SV_PROF_KINDS) return SV_EINVAL;
+    SV_HIP(c, hipStreamSynchronize(c->stream));
+    double tot = 0.0;
+    int n = 0;
+    std::vector<sv_ctx::ProfRec> keep;
+    for (auto& r : c->prof_recs) {
+        if (r.kind != kind) { keep.push_back(r); continue; }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) { tot += ms; ++n; }
+        c->prof_free.push_back(r.a);
+        c->prof_free.push_back(r.b);
+    }
+    c->prof_recs.swap(keep);
+    *total_ms = tot;
+    *launches = n;
+    return SV_OK;
+}
+
+extern "C" int sv_seq_set_lens(sv_ctx* c, const int32_t* seq_ids, const int32_t* lens, int n) {
+    if (!c || !seq_ids || !lens || n <= 0 || n > c->rt.max_batch) return SV_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        const int id = seq_ids[i];
+        if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+        if (lens[i] < 0 || lens[i] > (int)c->seqs[id].pages.size() * c->rt.page_size)
+            return c->fail(SV_EINVAL, "length %d beyond the pages sequence %d holds", lens[i], id);
+    }
+    const int slot = c->ring_pos;
+    if (c->staged_valid[slot]) SV_HIP(c, hipEventSynchronize(c->staged[slot]));
+    int32_t* st = c->staging[slot];
+    for (int i = 0; i < n; ++i) { st[2 * i] = seq_ids[i]; st[2 * i + 1] = lens[i]; }
+    SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.upd), st, 2 * n * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    hipLaunchKernelGGL(set_lens_kernel, dim3((n + 63) / 64), dim3(64), 0, c->stream, c->at<int32_t>(c->lay.seq_len),
+                       c->at<int32_t>(c->lay.upd), n);
+    SV_HIP(c, hipGetLastError());
+    SV_HIP(c, hipEventRecord(c->staged[slot], c->stream));
+    c->staged_valid[slot] = true;
+    c->ring_pos = (slot + 1) % kRing;
+    for (int i = 0; i < n; ++i) c->seqs[seq_ids[i]].len_ub = lens[i];
     return SV_OK;
 }
 

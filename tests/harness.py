@@ -92,12 +92,17 @@ class Case:
 
 def compare_step(r: OV.StepResult, g: dict, dtype: str, k: int):
     """Logits within tolerance everywhere; accepted lengths, kept chains and emitted tokens identical,
-    except for requests where some decision the oracle took had a margin below MARGIN.
-    Returns (max logit error, number of exempted requests, list of requests that diverged)."""
-    err = float(np.max(np.abs(g["logits"].astype(np.float64) - r.logits)))
+    except for requests where a decision the oracle took was closer than the margin.  The margin is
+    MARGIN (1e-3), widened to twice the logit error actually seen on that request's rows: two sets of
+    logits that differ by e cannot be expected to agree on a decision whose margin is below 2e (both
+    the compared logit and the log-sum-exp move).  Mismatches with a margin above 1e-3 are counted
+    separately.  Returns (max logit error, number of exempted requests, requests that diverged)."""
+    diff = np.abs(g["logits"].astype(np.float64) - r.logits)
+    err = float(np.max(diff))
     assert err < LOGIT_TOL[dtype], f"logits differ by {err}"
     B = len(r.accepted_len)
     exempt, diverged = 0, []
+    compare_step.beyond_margin = 0
     for b in range(B):
         same = (g["accepted_len"][b] == r.accepted_len[b] and g["best_chain"][b] == r.best_chain[b]
                 and np.array_equal(g["out_tokens"][b], r.out_tokens[b]))
@@ -105,9 +110,16 @@ def compare_step(r: OV.StepResult, g: dict, dtype: str, k: int):
         if same:
             continue
         margin = min(float(np.min(r.accept_margin[b])), float(np.min(r.draw_margin[b])))
-        assert margin < MARGIN, (f"request {b}: device a={g['accepted_len'][b]} tokens={g['out_tokens'][b]} "
-                                 f"chain={g['best_chain'][b]} vs oracle a={r.accepted_len[b]} "
-                                 f"tokens={r.out_tokens[b]} chain={r.best_chain[b]}; smallest margin {margin}")
+        allowed = max(MARGIN, 2.0 * float(np.max(diff[b])))
+        assert margin < allowed, (f"request {b}: device a={g['accepted_len'][b]} tokens={g['out_tokens'][b]} "
+                                  f"chain={g['best_chain'][b]} vs oracle a={r.accepted_len[b]} "
+                                  f"tokens={r.out_tokens[b]} chain={r.best_chain[b]}; smallest margin {margin}, "
+                                  f"logit error on its rows {float(np.max(diff[b]))}")
+        if margin >= MARGIN:
+            compare_step.beyond_margin += 1
         exempt += 1
         diverged.append(b)
     return err, exempt, diverged
+
+
+compare_step.beyond_margin = 0
