@@ -39,9 +39,13 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     const int kend = min(kbeg + a.chunk_keys, total);
     const int G = a.Hq / a.Hkv, rows = G * a.n;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // wave index as a scalar: tile numbers, page-table reads and page addresses stay on the scalar unit
+    // (a vector page-table load would have to be waited for with vmcnt(0), draining the K/V prefetch)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lg = lane >> 4;
     const bf16_t* pool = reinterpret_cast<const bf16_t*>(a.pool);
+    const int page_shift = 31 - __builtin_clz(a.geom.page_size), page_mask = a.geom.page_size - 1;
     const int32_t* pages = a.page_table + (int64_t)seq * a.max_pages_per_seq;
 
     // Q^T operand: lane holds row rt*16 + l16, head_dim slice kk*32 + lg*8 .. +8
@@ -69,18 +73,19 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     }
 
     floatx4 o[8][R];
-    float m_run[R], l_run[R];
+    float m_run[R], mc[R], l_run[R];      // reference maximum (raw score), the same times scale*log2(e), partial sum
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
         m_run[rt] = -INFINITY;
+        mc[rt] = 0.f;
         l_run[rt] = 0.f;
 #pragma unroll
         for (int ht = 0; ht < 8; ++ht) o[ht][rt] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
     auto load_tile = [&](int key0, KTile& t) {
-        const int page = pages[key0 / a.geom.page_size];
-        const int off = key0 % a.geom.page_size;
+        const int page = pages[key0 >> page_shift];
+        const int off = key0 & page_mask;
         const bf16_t* kp = pool + kv_k_index(a.geom, a.layer, page, hkv, off, 0);
         const bf16_t* vp = pool + kv_v_index(a.geom, a.layer, page, hkv, off, 0);
 #pragma unroll
@@ -95,15 +100,11 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
                 t.v[ht][hf] = *reinterpret_cast<const u32x2*>(vp + (ht * 16 + l16) * kVBlk + hf * 16 + lg * 4);
     };
 
-    const int ntiles = (kend - kbeg + TILE_KEYS - 1) / TILE_KEYS;
-    KTile cur, nxt;
-    int it = wave;
-    if (it < ntiles) load_tile(kbeg + it * TILE_KEYS, cur);
-    for (; it < ntiles; it += 4) {
-        const int key0 = kbeg + it * TILE_KEYS;
-        if (it + 4 < ntiles) load_tile(key0 + 4 * TILE_KEYS, nxt);
-
-        // S^T = K Q^T : s[kb][rt][i] <-> key key0 + kb*16 + 4*lg + i, row rt*16 + l16
+    // One 32-key tile: scores, online softmax, PV.  key0 >= kInvalidKey marks a tile past the end of the
+    // chunk (its registers hold a re-load of the last tile): every key is masked and nothing changes.
+    constexpr int kInvalidKey = 0x3fffffff;
+    auto process = [&](const KTile& t, int key0) {
+        // S^T = K Q^T (raw dot products): s[kb][rt][i] <-> key key0 + kb*16 + 4*lg + i, row rt*16 + l16
         floatx4 s[2][R];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -113,8 +114,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, cur.k[kb][kk]), __builtin_bit_cast(bf16x8, qf[rt][kk]), acc, 0, 0, 0);
-                s[kb][rt] = acc * scale_log2e;
+                        __builtin_bit_cast(bf16x8, t.k[kb][kk]), __builtin_bit_cast(bf16x8, qf[rt][kk]), acc, 0, 0, 0);
+                s[kb][rt] = acc;
             }
         if (key0 + TILE_KEYS > L) {   // tile touches the new rows or the end: apply visibility
 #pragma unroll
@@ -131,56 +132,88 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
                         s[kb][rt][i] = vis ? s[kb][rt][i] : -INFINITY;
                     }
         }
+        // Lazy reference maximum.  The softmax reference m_ref of a row is common to the 4 lane groups
+        // that share the row (they feed one MFMA accumulator) and is only moved when some score would
+        // make 2^(c(s - m_ref)) exceed 2^16 (or on the row's first visible key): fp32 has the range to
+        // spare, and the cross-lane reduction + accumulator rescale leave the per-tile path.
+        bool trig = false;
+        float lmax[R];
 #pragma unroll
         for (int rt = 0; rt < R; ++rt) {
-            float mx = fmaxf(fmaxf(fmaxf(s[0][rt][0], s[0][rt][1]), fmaxf(s[0][rt][2], s[0][rt][3])),
+            lmax[rt] = fmaxf(fmaxf(fmaxf(s[0][rt][0], s[0][rt][1]), fmaxf(s[0][rt][2], s[0][rt][3])),
                              fmaxf(fmaxf(s[1][rt][0], s[1][rt][1]), fmaxf(s[1][rt][2], s[1][rt][3])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[rt], mx);
-            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = exp2f(m_run[rt] - m_safe);
-            m_run[rt] = m_new;
-            float p[8];
+            trig |= ((m_run[rt] == -INFINITY) & (lmax[rt] > -INFINITY)) | (fmaf(lmax[rt], scale_log2e, -mc[rt]) > 16.0f);
+        }
+        if (__any(trig)) {
+#pragma unroll
+            for (int rt = 0; rt < R; ++rt) {
+                float mx = lmax[rt];
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[rt], mx);
+                const float mc_new = m_new == -INFINITY ? 0.f : m_new * scale_log2e;
+                const float alpha = m_run[rt] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mc[rt] - mc_new);
+                l_run[rt] *= alpha;
+#pragma unroll
+                for (int ht = 0; ht < 8; ++ht) o[ht][rt] = o[ht][rt] * alpha;
+                m_run[rt] = m_new;
+                mc[rt] = mc_new;
+            }
+        }
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+            floatx2 p[4];
             float psum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                p[i] = exp2f(s[0][rt][i] - m_safe);
-                p[4 + i] = exp2f(s[1][rt][i] - m_safe);
-                psum += p[i] + p[4 + i];
+            for (int i = 0; i < 2; ++i) {
+                p[i] = floatx2{__builtin_amdgcn_exp2f(fmaf(s[0][rt][2 * i], scale_log2e, -mc[rt])),
+                               __builtin_amdgcn_exp2f(fmaf(s[0][rt][2 * i + 1], scale_log2e, -mc[rt]))};
+                p[2 + i] = floatx2{__builtin_amdgcn_exp2f(fmaf(s[1][rt][2 * i], scale_log2e, -mc[rt])),
+                                   __builtin_amdgcn_exp2f(fmaf(s[1][rt][2 * i + 1], scale_log2e, -mc[rt]))};
+                psum += (p[i].x + p[i].y) + (p[2 + i].x + p[2 + i].y);
             }
-            l_run[rt] = l_run[rt] * alpha + psum;
+            l_run[rt] += psum;
             // P goes to the MFMA as three bf16 terms (24 significant bits in all).  One bf16 term would
             // leave a 2^-9 relative error in the output however many keys there are (V has zero mean, so
             // the output is as small as the error's random walk); two terms leave 2^-17, still enough to
             // move every few-hundredth output across a bf16 rounding boundary.
             u32x4 pf[3];
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                uint32_t w[4];
+            for (int tm = 0; tm < 3; ++tm)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const bf16_t a0 = f2bf(p[2 * i]), a1 = f2bf(p[2 * i + 1]);
-                    p[2 * i] -= bf2f(a0);
-                    p[2 * i + 1] -= bf2f(a1);
-                    w[i] = (uint32_t)a0 | ((uint32_t)a1 << 16);
+                    const bf16x2 hb = __builtin_convertvector(p[i], bf16x2);
+                    pf[tm][i] = __builtin_bit_cast(uint32_t, hb);
+                    if (tm < 2) p[i] = p[i] - __builtin_convertvector(hb, floatx2);
                 }
-                pf[t] = u32x4{w[0], w[1], w[2], w[3]};
-            }
 #pragma unroll
             for (int ht = 0; ht < 8; ++ht) {
-                o[ht][rt] = o[ht][rt] * alpha;
-                u32x4 vf = {cur.v[ht][0][0], cur.v[ht][0][1], cur.v[ht][1][0], cur.v[ht][1][1]};
+                const u32x4 vf = {t.v[ht][0][0], t.v[ht][0][1], t.v[ht][1][0], t.v[ht][1][1]};
 #pragma unroll
-                for (int t = 2; t >= 0; --t)
+                for (int tm = 2; tm >= 0; --tm)
                     o[ht][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                                        __builtin_bit_cast(bf16x8, pf[t]), o[ht][rt], 0, 0, 0);
+                                                                        __builtin_bit_cast(bf16x8, pf[tm]), o[ht][rt], 0, 0, 0);
             }
         }
-        cur = nxt;
+    };
+
+    // Two tiles per trip, ping-pong between two register sets.  Loads are unconditional (past the end
+    // they re-load the last tile) so that the wait before a tile's math only has to cover that tile's
+    // loads and the other set stays in flight.
+    const int ntiles = (kend - kbeg + TILE_KEYS - 1) / TILE_KEYS;
+    const int last = ntiles - 1;
+    KTile ta, tb;
+    load_tile(kbeg + min(wave, last) * TILE_KEYS, ta);
+    for (int it = wave; it < ntiles; it += 8) {
+        load_tile(kbeg + min(it + 4, last) * TILE_KEYS, tb);
+        process(ta, kbeg + it * TILE_KEYS);
+        load_tile(kbeg + min(it + 8, last) * TILE_KEYS, ta);
+        process(tb, it + 4 < ntiles ? kbeg + (it + 4) * TILE_KEYS : kInvalidKey);
     }
 
-    // ---- merge the four waves of the group through LDS ----
+    // ---- merge the four waves of the group through LDS (maxima in log2 units from here on) ----
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) m_run[rt] = m_run[rt] == -INFINITY ? -INFINITY : mc[rt];
     constexpr int RP = 16 * R;
     __shared__ float m_sh[4][RP], l_sh[4][RP];
     __shared__ float o_sh[HD][RP + 1];
@@ -310,7 +343,8 @@ int attn_rows_pad(int n, int group) {
 hipError_t attention(const AttnArgs& a, hipStream_t st) {
     const float scale = 1.0f / sqrtf((float)a.hd);
     const int G = a.Hq / a.Hkv;
-    const int rp = (!a.force_generic && a.dtype == 1 && a.hd == HD && a.geom.page_size % TILE_KEYS == 0 && a.chunk_keys % 128 == 0)
+    const int rp = (!a.force_generic && a.dtype == 1 && a.hd == HD && a.geom.page_size % TILE_KEYS == 0 &&
+                    (a.geom.page_size & (a.geom.page_size - 1)) == 0 && a.chunk_keys % 128 == 0)
                        ? attn_rows_pad(a.n, G) : 0;
     if (rp) {
         const float sl2 = scale * 1.44269504088896340736f;

@@ -214,6 +214,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
         return SV_EINVAL;
     if (m->n_experts > 0) return SV_EUNSUPPORTED;                 // mixture-of-experts FFN: not built yet
     if (m->head_dim != 64 && m->head_dim != 128) return SV_EUNSUPPORTED;
+    if (m->d_model % 4 != 0 || m->d_model > 8192) return SV_EUNSUPPORTED;   // RMSNorm kernel: float4 pieces, <= 8 per thread
     if (m->dtype == SV_BF16) {
         const int qw = m->n_q_heads * m->head_dim, qkvw = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
         if (!gemm_bf16_shape_ok(qkvw, m->d_model, 1) || !gemm_bf16_shape_ok(m->d_model, qw, 1) ||

@@ -35,65 +35,97 @@ __global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restr
     for (int i = threadIdx.x; i < d; i += blockDim.x) h[(int64_t)t * d + i] = Store<T>::load(src + i);
 }
 
-template <typename T>
+// One 256-thread group per row.  Each thread owns up to NV float4 pieces of the row; the loads of the
+// residual and of every split-K partial product are issued before the first use, so the row costs a
+// few memory round trips rather than one per element.
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int S,
                                                           int64_t part_stride, const T* __restrict__ w,
                                                           T* __restrict__ a, int d, float eps) {
     __shared__ float red[4];
     const int t = blockIdx.x;
-    float* hr = h + (int64_t)t * d;
+    const int nq = d >> 2;                               // float4 pieces per row
+    floatx4* hr = reinterpret_cast<floatx4*>(h + (int64_t)t * d);
+    floatx4 x[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int i = threadIdx.x + v * 256;
+        x[v] = i < nq ? hr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    for (int s = 0; s < S; ++s) {
+        const floatx4* pr = reinterpret_cast<const floatx4*>(part + s * part_stride + (int64_t)t * d);
+        floatx4 y[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int i = threadIdx.x + v * 256;
+            y[v] = i < nq ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int v = 0; v < NV; ++v) x[v] = x[v] + y[v];
+    }
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float x = hr[i];
-        for (int s = 0; s < S; ++s) x += part[s * part_stride + (int64_t)t * d + i];
-        hr[i] = x;
-        ss = fmaf(x, x, ss);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int i = threadIdx.x + v * 256;
+        if (i < nq) {
+            if (S) hr[i] = x[v];
+            ss = fmaf(x[v][0], x[v][0], ss);
+            ss = fmaf(x[v][1], x[v][1], ss);
+            ss = fmaf(x[v][2], x[v][2], ss);
+            ss = fmaf(x[v][3], x[v][3], ss);
+        }
     }
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float tot = red[0] + red[1] + red[2] + red[3];
     const float r = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) Store<T>::store(a + (int64_t)t * d + i, hr[i] * r * Store<T>::load(w + i));
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int i = threadIdx.x + v * 256;
+        if (i < nq) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                Store<T>::store(a + (int64_t)t * d + 4 * i + e, x[v][e] * r * Store<T>::load(w + 4 * i + e));
+        }
+    }
 }
 
+// One wave per (row, head): q and k heads are rotated, k and v heads go to the row's cache slot.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(RopeAppend p) {
-    const int t = blockIdx.x, b = t / p.n;
+__global__ __launch_bounds__(64) void rope_append_kernel(RopeAppend p) {
+    const int t = blockIdx.x, head = blockIdx.y, b = t / p.n;
     const int hd = p.hd, half = hd / 2;
     const int ncol = (p.Hq + 2 * p.Hkv) * hd;
     const int64_t stride = (int64_t)p.T * ncol;
-    const float* src = p.qkv_part + (int64_t)t * ncol;
+    const float* src = p.qkv_part + (int64_t)t * ncol + head * hd;
     const int slot = p.row_slot[t];
     const int page = p.page_table[(int64_t)p.batch_seq[b] * p.max_pages_per_seq + slot / p.geom.page_size];
     const int tok = slot % p.geom.page_size;
     T* pool = reinterpret_cast<T*>(p.pool);
-    auto val = [&](int col) {
-        float x = 0.f;
-        for (int s = 0; s < p.S; ++s) x += src[s * stride + col];
-        return x;
-    };
-    // rotated heads: q heads then k heads, one (head, pair) per iteration
-    const int nrot = (p.Hq + p.Hkv) * half;
-    for (int e = threadIdx.x; e < nrot; e += 256) {
-        const int head = e / half, i = e % half;
-        const float c = p.rope[((int64_t)t * half + i) * 2], s = p.rope[((int64_t)t * half + i) * 2 + 1];
-        const float x1 = val(head * hd + i), x2 = val(head * hd + i + half);
-        const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
-        if (head < p.Hq) {
-            T* q = reinterpret_cast<T*>(p.q_out) + ((int64_t)t * p.Hq + head) * hd;
-            Store<T>::store(q + i, o1);
-            Store<T>::store(q + i + half, o2);
-        } else {
-            const int kh = head - p.Hq;
-            Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i), o1);
-            Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i + half), o2);
+    for (int i = threadIdx.x; i < half; i += 64) {
+        float x1 = 0.f, x2 = 0.f;
+        for (int s = 0; s < p.S; ++s) {
+            x1 += src[s * stride + i];
+            x2 += src[s * stride + i + half];
         }
-    }
-    const int nv = p.Hkv * hd;
-    for (int e = threadIdx.x; e < nv; e += 256) {
-        const int kh = e / hd, i = e % hd;
-        Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i), val((p.Hq + p.Hkv) * hd + e));
+        if (head < p.Hq + p.Hkv) {
+            const float c = p.rope[((int64_t)t * half + i) * 2], sn = p.rope[((int64_t)t * half + i) * 2 + 1];
+            const float o1 = x1 * c - x2 * sn, o2 = x2 * c + x1 * sn;
+            if (head < p.Hq) {
+                T* q = reinterpret_cast<T*>(p.q_out) + ((int64_t)t * p.Hq + head) * hd;
+                Store<T>::store(q + i, o1);
+                Store<T>::store(q + i + half, o2);
+            } else {
+                const int kh = head - p.Hq;
+                Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i), o1);
+                Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i + half), o2);
+            }
+        } else {
+            const int kh = head - p.Hq - p.Hkv;
+            Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i), x1);
+            Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i + half), x2);
+        }
     }
 }
 
@@ -153,23 +185,32 @@ hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, floa
     return hipGetLastError();
 }
 
-hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
-                       hipStream_t st) {
-    const int64_t stride = (int64_t)T * d;
-    if (dtype == 1)
-        hipLaunchKernelGGL(add_rmsnorm_kernel<bf16_t>, dim3(T), dim3(256), 0, st, h, part, S, stride,
-                           (const bf16_t*)w, (bf16_t*)a, d, eps);
+template <typename T>
+static hipError_t add_rmsnorm_t(float* h, const float* part, int S, const T* w, T* a, int T_, int d, float eps, hipStream_t st) {
+    const int64_t stride = (int64_t)T_ * d;
+    const int nq = d / 4;
+    if (d % 4 != 0 || nq > 256 * 8) return hipErrorInvalidValue;
+    if (nq <= 256 * 2)
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 2>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps);
+    else if (nq <= 256 * 4)
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 4>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps);
     else
-        hipLaunchKernelGGL(add_rmsnorm_kernel<float>, dim3(T), dim3(256), 0, st, h, part, S, stride, (const float*)w,
-                           (float*)a, d, eps);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 8>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps);
     return hipGetLastError();
 }
 
+hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
+                       hipStream_t st) {
+    if (dtype == 1) return add_rmsnorm_t<bf16_t>(h, part, S, (const bf16_t*)w, (bf16_t*)a, T, d, eps, st);
+    return add_rmsnorm_t<float>(h, part, S, (const float*)w, (float*)a, T, d, eps, st);
+}
+
 hipError_t rope_append(const RopeAppend& p, hipStream_t st) {
+    dim3 grid(p.T, p.Hq + 2 * p.Hkv);
     if (p.dtype == 1)
-        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(p.T), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, st, p);
     else
-        hipLaunchKernelGGL(rope_append_kernel<float>, dim3(p.T), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(rope_append_kernel<float>, grid, dim3(64), 0, st, p);
     return hipGetLastError();
 }
 
