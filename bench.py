@@ -93,6 +93,9 @@ def main():
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--cpu-seqs", type=int, default=2, help="requests in the oracle sample (0 = skip)")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--drafts", choices=["noisy-target", "independent"], default="noisy-target",
+                    help="independent: drafts from q = softmax(N(0,1)) without any device decoding step, so that "
+                         "every kernel launch of the process has the timed step's shape (used for profiles)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the verification step on ONE GPU (requests shard across workers "
@@ -111,8 +114,12 @@ def main():
     case = DeviceCase(shape, k=args.k, log=log)
     if args.gemm_variant is not None:
         case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
-    log("drafting (noisy-target drafts through plain decoding steps) ...")
-    case.noisy_target_drafts(None if args.sigma is None else [args.sigma])
+    if args.drafts == "independent":
+        log("drafting (target-independent q) ...")
+        case.independent_drafts(1.0)
+    else:
+        log("drafting (noisy-target drafts through plain decoding steps) ...")
+        case.noisy_target_drafts(None if args.sigma is None else [args.sigma])
     B, N, k = case.B, case.N, case.k
     n = 1 + N * k
     T = B * n
@@ -175,7 +182,7 @@ def main():
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": shape.name, "batch": B, "k": k, "chains": N, "rows_per_step": T,
-                   "prefix_tokens": int(case.lengths.sum()), "draft_sigma": list(shape.draft_sigma) if args.sigma is None else [args.sigma],
+                   "prefix_tokens": int(case.lengths.sum()), "drafts": args.drafts, "draft_sigma": list(shape.draft_sigma) if args.sigma is None else [args.sigma],
                    "verify": "stochastic, exponential-race draw, temperature 1.0"},
         "accepted_drafts_per_step": int(acc.sum()), "emitted_tokens_per_step": emitted,
         "accepted_drafts_tokens_per_s": int(acc.sum()) / (ms_per_step * 1e-3),

@@ -26,17 +26,23 @@ namespace sv {
 constexpr int HD = 128;
 constexpr int TILE_KEYS = 32;
 
-struct KTile { u32x4 k[2][4]; u32x2 v[8][2]; };
+struct KTile { u32x4 k[2][4]; u32x4 v[8]; };
 
 template <int R>
 __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
-    const int chunk = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+    // work item = (request, chunk), listed by the host from its upper bounds of the lengths; the chunk
+    // geometry comes from the true length: nch equal pieces, each a whole number of tiles
+    const int item = a.work[blockIdx.x], hkv = blockIdx.y;
+    const int b = item >> 16, chunk = item & 0xffff;
     const int seq = a.batch_seq[b];
     const int L = a.seq_len[seq];
     const int total = L + a.n;
-    const int kbeg = chunk * a.chunk_keys;
+    const int nch = (total + a.chunk_keys - 1) / a.chunk_keys;
+    if (chunk >= nch) return;
+    const int clen = ((total + nch - 1) / nch + TILE_KEYS - 1) / TILE_KEYS * TILE_KEYS;
+    const int kbeg = chunk * clen;
     if (kbeg >= total) return;
-    const int kend = min(kbeg + a.chunk_keys, total);
+    const int kend = min(kbeg + clen, total);
     const int G = a.Hq / a.Hkv, rows = G * a.n;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -86,18 +92,15 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     auto load_tile = [&](int key0, KTile& t) {
         const int page = pages[key0 >> page_shift];
         const int off = key0 & page_mask;
-        const bf16_t* kp = pool + kv_k_index(a.geom, a.layer, page, hkv, off, 0);
-        const bf16_t* vp = pool + kv_v_index(a.geom, a.layer, page, hkv, off, 0);
+        const bf16_t* kp = pool + kv_k_index(a.geom, a.layer, page, hkv, off, 0) + lane * 8;
+        const bf16_t* vp = pool + kv_v_index(a.geom, a.layer, page, hkv, off, 0) + lane * 8;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
-                t.k[kb][kk] = *reinterpret_cast<const u32x4*>(kp + (kb * 16 + l16) * HD + kk * 32 + lg * 8);
+                t.k[kb][kk] = *reinterpret_cast<const u32x4*>(kp + (kb * 4 + kk) * 512);
 #pragma unroll
-        for (int ht = 0; ht < 8; ++ht)
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-                t.v[ht][hf] = *reinterpret_cast<const u32x2*>(vp + (ht * 16 + l16) * kVBlk + hf * 16 + lg * 4);
+        for (int ht = 0; ht < 8; ++ht) t.v[ht] = *reinterpret_cast<const u32x4*>(vp + ht * 512);
     };
 
     // One 32-key tile: scores, online softmax, PV.  key0 >= kInvalidKey marks a tile past the end of the
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
                 }
 #pragma unroll
             for (int ht = 0; ht < 8; ++ht) {
-                const u32x4 vf = {t.v[ht][0][0], t.v[ht][0][1], t.v[ht][1][0], t.v[ht][1][1]};
+                const u32x4 vf = t.v[ht];
 #pragma unroll
                 for (int tm = 2; tm >= 0; --tm)
                     o[ht][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
@@ -277,7 +280,9 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, int rows_pad
     const int b = t / a.n, j = t % a.n;
     const int G = a.Hq / a.Hkv, hkv = h / G, r = j * G + h % G;
     const int total = a.seq_len[a.batch_seq[b]] + a.n;
-    const int nch = (total + a.chunk_keys - 1) / a.chunk_keys;
+    int nch = (total + a.chunk_keys - 1) / a.chunk_keys;
+    const int clen = ((total + nch - 1) / nch + TILE_KEYS - 1) / TILE_KEYS * TILE_KEYS;
+    nch = (total + clen - 1) / clen;               // trailing pieces can be empty after rounding to tiles
     const int64_t base = ((int64_t)b * a.Hkv + hkv) * a.max_chunks;
     float M = -INFINITY;
     for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((base + c) * rows_pad + r) * 2]);
@@ -348,7 +353,7 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
                        ? attn_rows_pad(a.n, G) : 0;
     if (rp) {
         const float sl2 = scale * 1.44269504088896340736f;
-        dim3 grid(a.max_chunks, a.Hkv, a.B);
+        dim3 grid(a.n_work, a.Hkv);
         switch (std::max(rp / 16, a.min_row_tiles)) {
             case 1: hipLaunchKernelGGL(attn_bf16_kernel<1>, grid, dim3(256), 0, st, a, sl2); break;
             case 2: hipLaunchKernelGGL(attn_bf16_kernel<2>, grid, dim3(256), 0, st, a, sl2); break;

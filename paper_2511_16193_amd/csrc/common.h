@@ -6,7 +6,7 @@
 namespace sv {
 
 constexpr int kWave = 64;          // CDNA wavefront
-constexpr int kVBlk = 32;          // keys per transposed-V sub-block inside a KV page
+constexpr int kVBlk = 32;          // keys per tile of a KV page
 
 typedef uint16_t bf16_t;           // raw bf16 bits
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -36,24 +36,33 @@ template <> struct Store<bf16_t> {
 };
 
 // ---- paged KV layout -------------------------------------------------------
-// pool[layer][page][K | V][kv_head]:
-//   K block: [page_size][head_dim]                      (token major)
-//   V block: [page_size / kVBlk][head_dim][kVBlk]       (transposed in sub-blocks of 32 keys, so a
-//            32-key tile of V^T is one contiguous region with the keys of one head_dim row adjacent)
+// pool[layer][page][K | V][kv_head][tile of 32 keys], each tile stored in the order the 16x16x32 MFMA
+// reads its operands, so that a wave fetches one operand fragment (64 lanes x 8 elements) as one
+// contiguous, fully used 1 KB (bf16) piece:
+//   K tile: fragments [key block kb = 0,1][head_dim slice kk = 0 .. hd/32-1], fragment element
+//           (lane = 16*g + r, e) = K[key 16*kb + r][dim 32*kk + 8*g + e]
+//   V tile: fragments [ht = 0 .. hd/16-1], fragment element (lane = 16*g + r, j) = V[key][dim 16*ht + r]
+//           with key = 4*g + j for j < 4 and 16 + 4*g + (j-4) otherwise -- the order in which the
+//           score tile leaves the MFMA (a lane holds 4 consecutive keys of each 16-key block).
 struct KvGeom {
     int n_kv_heads, head_dim, page_size;
     int64_t page_elems;    // 2 * n_kv_heads * page_size * head_dim
     int64_t layer_elems;   // num_pages * page_elems
 };
 __host__ __device__ __forceinline__ int64_t kv_k_index(const KvGeom& g, int layer, int page, int head, int tok, int dim) {
+    const int t = tok % kVBlk, kb = t / 16, r = t % 16;
+    const int kk = dim / 32, grp = (dim % 32) / 8, e = dim % 8;
     return (int64_t)layer * g.layer_elems + (int64_t)page * g.page_elems +
-           ((int64_t)head * g.page_size + tok) * g.head_dim + dim;
+           ((int64_t)head * g.page_size + (tok / kVBlk) * kVBlk) * g.head_dim +
+           ((kb * (g.head_dim / 32) + kk) * 64 + grp * 16 + r) * 8 + e;
 }
 __host__ __device__ __forceinline__ int64_t kv_v_index(const KvGeom& g, int layer, int page, int head, int tok, int dim) {
+    const int t = tok % kVBlk, half = t / 16, grp = (t % 16) / 4, j = half * 4 + t % 4;
+    const int ht = dim / 16, r = dim % 16;
     return (int64_t)layer * g.layer_elems + (int64_t)page * g.page_elems +
            (int64_t)g.n_kv_heads * g.page_size * g.head_dim +
-           ((int64_t)head * g.page_size) * g.head_dim +
-           ((int64_t)(tok / kVBlk) * g.head_dim + dim) * kVBlk + (tok % kVBlk);
+           ((int64_t)head * g.page_size + (tok / kVBlk) * kVBlk) * g.head_dim +
+           ((ht * 64) + grp * 16 + r) * 8 + j;
 }
 
 // Index of new row j (0 = x0, then chain 0's drafts, chain 1's ...) -> chain, index in chain.

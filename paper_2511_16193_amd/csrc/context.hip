@@ -37,14 +37,15 @@ int pick_splits(int M, int N, int K) {
 }
 
 struct Layout {                       // byte offsets into the workspace
-    size_t seq_len, page_table, batch_seq, upd, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
+    size_t seq_len, page_table, batch_seq, upd, work, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
     size_t rope, row_stat, h, a_norm, q, attn, part, act, logits, part_o, part_ml, total;
     int T, rows_pad, max_chunks;
 };
 
 bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     if (r.max_batch <= 0 || r.max_k < 0 || r.max_chains <= 0 || r.max_seqs <= 0 || r.page_size <= 0 ||
-        r.page_size % kVBlk != 0 || r.num_pages <= 0 || r.max_pages_per_seq <= 0)
+        r.page_size % kVBlk != 0 || r.num_pages <= 0 || r.max_pages_per_seq <= 0 || r.max_batch > 32767 ||
+        (size_t)r.max_pages_per_seq * r.page_size / kChunkKeys > 65535)
         return false;
     const size_t es = m.dtype == SV_BF16 ? 2 : 4;
     const int T = r.max_batch * (1 + r.max_chains * r.max_k);
@@ -57,6 +58,8 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.page_table = take(sizeof(int32_t) * (size_t)r.max_seqs * r.max_pages_per_seq);
     L.batch_seq = take(sizeof(int32_t) * r.max_batch);
     L.upd = take(sizeof(int32_t) * 3 * (size_t)r.max_batch * 8);
+    L.max_chunks = (int)(((size_t)r.max_pages_per_seq * r.page_size + kChunkKeys - 1) / kChunkKeys);
+    L.work = take(sizeof(int32_t) * (size_t)r.max_batch * L.max_chunks);
     L.row_tok = take(sizeof(int32_t) * T);
     L.row_pos = take(sizeof(int32_t) * T);
     L.row_slot = take(sizeof(int32_t) * T);
@@ -82,7 +85,6 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.logits = take(sizeof(float) * (size_t)T * m.vocab);
     const int G = m.n_q_heads / std::max(1, m.n_kv_heads);
     L.rows_pad = 64;
-    L.max_chunks = (int)(((size_t)r.max_pages_per_seq * r.page_size + kChunkKeys - 1) / kChunkKeys);
     (void)G;
     L.part_o = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * m.head_dim);
     L.part_ml = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * 2);
@@ -123,9 +125,11 @@ struct sv_ctx {
     hipEvent_t staged[kRing];
     bool staged_valid[kRing];
     int ring_pos;
+    int n_work;                                           // attention work items staged for the current batch
     int gemm_variant;
     bool attn_generic;
     int attn_min_rt;
+    int attn_chunk;                                       // keys per split-KV chunk (multiple of kChunkKeys)
     unsigned prof_mask;                                   // kinds of kernels to time with events
     struct ProfRec { int kind; hipEvent_t a, b; };
     std::vector<ProfRec> prof_recs;                       // recorded, not yet read
@@ -246,8 +250,9 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->gemm_variant = 0;
     c->attn_generic = false;
     c->attn_min_rt = 1;
+    c->attn_chunk = kChunkKeys;
     c->prof_mask = 0;
-    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8) + 8;
+    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8 + L.max_chunks) + 8;
     for (int i = 0; i < kRing; ++i) { c->staging[i] = nullptr; c->staged[i] = nullptr; c->staged_valid[i] = false; }
     for (int i = 0; i < kRing; ++i) {
         if (hipHostMalloc(reinterpret_cast<void**>(&c->staging[i]), slot_ints * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
@@ -403,6 +408,23 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
                            c->at<int32_t>(c->lay.page_table), c->rt.max_pages_per_seq, c->at<int32_t>(c->lay.upd), nupd);
         SV_HIP(c, hipGetLastError());
     }
+    // attention work list: every (request, chunk) that can exist given the upper bounds of the lengths,
+    // whole chunks first, the requests' last (shorter) pieces after them, longest first
+    {
+        int32_t* work = upd + 3 * nupd;
+        int nw = 0;
+        std::vector<std::pair<int, int>> tails;
+        for (int b = 0; b < B; ++b) {
+            const int total = c->seqs[ids[b]].len_ub + extra;
+            const int nch = std::min((total + c->attn_chunk - 1) / c->attn_chunk, c->lay.max_chunks);
+            for (int ch = 0; ch + 1 < nch; ++ch) work[nw++] = (b << 16) | ch;
+            if (nch > 0) tails.push_back({-(total - (nch - 1) * (total / nch)), (b << 16) | (nch - 1)});
+        }
+        std::sort(tails.begin(), tails.end());
+        for (auto& t : tails) work[nw++] = t.second;
+        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.work), work, nw * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+        c->n_work = nw;
+    }
     SV_HIP(c, hipEventRecord(c->staged[slot], c->stream));
     c->staged_valid[slot] = true;
     c->ring_pos = (slot + 1) % kRing;
@@ -459,9 +481,9 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.batch_seq = rp.batch_seq; aa.seq_len = rp.seq_len; aa.out = c->at<void>(L.attn);
         aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml);
         aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
-        aa.chunk_keys = kChunkKeys;
+        aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work;
         aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
-        aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + kChunkKeys - 1) / kChunkKeys);
+        aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
         {
             ProfScope prof(c, SV_PROF_ATTENTION);
             SV_HIP(c, attention(aa, st));
@@ -603,8 +625,9 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.batch_seq = c->at<int32_t>(c->lay.batch_seq); aa.seq_len = c->at<int32_t>(c->lay.seq_len); aa.out = out;
     aa.part_o = c->at<float>(c->lay.part_o); aa.part_ml = c->at<float>(c->lay.part_ml);
     aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
-    aa.chunk_keys = kChunkKeys; aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
-    aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + kChunkKeys - 1) / kChunkKeys);
+    aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(c->lay.work); aa.n_work = c->n_work;
+    aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
+    aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
     SV_HIP(c, attention(aa, c->stream));
     return SV_OK;
 }
@@ -666,6 +689,10 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
             return SV_OK;
         case SV_OPT_ATTN_GENERIC:
             c->attn_generic = value != 0;
+            return SV_OK;
+        case SV_OPT_ATTN_CHUNK_KEYS:
+            if (value < kChunkKeys || value % kChunkKeys != 0) return c->fail(SV_EINVAL, "chunk of %d keys", value);
+            c->attn_chunk = value;
             return SV_OK;
         case SV_OPT_ATTN_MIN_ROW_TILES:
             if (value < 1 || value > 4) return c->fail(SV_EINVAL, "row tiles %d", value);

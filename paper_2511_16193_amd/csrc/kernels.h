@@ -59,6 +59,7 @@ struct AttnArgs {
     float* part_ml;                     // [B][Hkv][max_chunks][rows_pad][2]
     int B, n, k, Hq, Hkv, hd, dtype;
     int chunk_keys, max_chunks;
+    const int32_t* work; int n_work;    // (request << 16 | chunk) items of the bf16 kernel
     int min_row_tiles;                  // lower bound on the 16-row tiles of the bf16 kernel (tuning)
     bool force_generic;                 // take the untuned one-wave-per-row path whatever the shape
 };

@@ -1,0 +1,105 @@
+"""Full-size parity: the benchmark workload (7B-shaped dense decoder, bf16, B=64, prefixes 1k-8k, k=4,
+stochastic verification) in the launch configuration bench.py times, checked against the oracle on a
+sample of requests (requests are independent through the whole step, so parity on a request is exact
+parity for that request) and against properties that hold for every request."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import model as M
+from oracle import verify as OV
+import workloads as W
+from harness import compare_step, LOGIT_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg2_full_size_sampled_requests_and_invariants():
+    from workloads.device_case import DeviceCase
+    shape = W.CONFIGS["cfg2"]
+    print(f"[full] building {shape.name} on the device", flush=True)
+    case = DeviceCase(shape)
+    # drafts that do not come from the device path: q = softmax(N(0,1)) independent of the target
+    case.independent_drafts(1.0)
+    B, N, k, V = case.B, case.N, case.k, shape.vocab
+    n = 1 + N * k
+    print("[full] device step", flush=True)
+    out = case.step(want_logits=True)
+    torch.cuda.synchronize()
+    acc = out["accepted_len"].cpu().numpy()
+    toks = out["out_tokens"].cpu().numpy()
+    drafts = case.drafts.cpu().numpy()
+
+    # ---- properties for all 64 requests ----
+    assert acc.min() >= 0 and acc.max() <= k
+    assert np.all(out["best_chain"].cpu().numpy() == 0)
+    for b in range(B):
+        a = int(acc[b])
+        assert np.array_equal(toks[b, :a], drafts[b, 0, :a])
+        assert 0 <= toks[b, a] < V
+        assert np.all(toks[b, a + 1:] == -1)
+        assert case.ver.seq_len(b) == int(case.lengths[b]) + a + 1
+    assert 0 < acc.sum() < B * k                      # both accepts and rejections occur
+
+    # ---- oracle on a sample: the shortest, the longest and one more request ----
+    sample = sorted({int(np.argmin(case.lengths)), int(np.argmax(case.lengths)), 7})
+    spec = M.ModelSpec(**shape.model_fields())
+    wn = W.weights_to_numpy(case.weights, lazy=True)
+    caches = []
+    for b in sample:
+        L = int(case.lengths[b])
+        c = M.SeqCache(spec, L + n + 1)
+        for l in range(shape.n_layers):
+            kk, vv = case.kv_block(b, l)
+            c.k[l][:L] = kk.float().cpu().numpy()
+            c.v[l][:L] = vv.float().cpu().numpy()
+        c.length = L
+        caches.append(c)
+    print(f"[full] oracle on requests {sample}", flush=True)
+    # the exponential-race draw is keyed by the request's index in the batch: run the oracle's sampler
+    # with the same keys by placing the sampled requests at their batch positions
+    x0 = case.x0.cpu().numpy().astype(np.int64)[sample]
+    q = case.draft_probs[sample].cpu().numpy()
+    u = case.uniforms[sample].cpu().numpy()
+    _, idx, vis = OV.new_token_layout(k, N)
+    tokens = np.concatenate([x0[:, None], drafts[sample].reshape(len(sample), N * k)], axis=1)
+    pos = np.array([c.length for c in caches])[:, None] + idx[None]
+    logits = M.forward(spec, wn, caches, tokens, pos, np.broadcast_to(vis, (len(sample), n, n)))
+    v = OV.verify_stochastic(logits, drafts[sample, 0], q[:, 0], u[:, 0], np.array(sample, dtype=np.uint64) * N,
+                             1.0, OV.SAMPLE_EXP_RACE)
+    dev_logits = out["logits"][sample].cpu().numpy().astype(np.float64)
+    diff = np.abs(dev_logits - logits)
+    rel_rms = float(np.sqrt(np.mean(diff ** 2)) / logits.std())
+    print(f"[full] logit error: max per sampled request {diff.reshape(len(sample), -1).max(axis=1)}, "
+          f"mean {diff.mean():.2e}, rms/std {rel_rms:.2e}", flush=True)
+    # Tolerance at full depth.  Both sides round activations to bf16 at the same points; a value that
+    # sits within the fp32-vs-fp64 difference of a rounding boundary rounds differently on the two
+    # sides (one unit = 2^-8 relative), which moves every output of the next projection by ~1e-4
+    # relative, which in turn flips a few per cent of the 18944 gated activations ... the difference
+    # settles at ~1e-3 of the residual stream per layer whatever the arithmetic, and adds up over the
+    # layers as a random walk (measured: max 1.7e-2 after 1 layer, 2.4e-2 after 2, 5.4e-2 after 8,
+    # 9.6e-2 after 28 on logits of standard deviation 1.2).  The 2e-2 bound holds per layer, not for 28:
+    # here the bound is 2e-2 * sqrt(n_layers) on the maximum and 3 % of the logits' spread on the rms.
+    assert diff.max() < LOGIT_TOL["bf16"] * np.sqrt(shape.n_layers)
+    assert rel_rms < 3e-2
+    beyond = 0
+    for i, b in enumerate(sample):
+        a = int(v.accepted[i])
+        want = list(drafts[b, 0, :a]) + [int(v.token[i])]
+        got = list(toks[b, :acc[b] + 1])
+        if a == acc[b] and want == got:
+            continue
+        margin = min(float(v.accept_margin[i]), float(v.draw_margin[i]))
+        allowed = max(1e-3, 2.0 * float(diff[i].max()))
+        assert margin < allowed, (b, got, want, margin, float(diff[i].max()))
+        beyond += margin >= 1e-3
+    print(f"[full] sampled requests beyond the 1e-3 margin: {beyond}", flush=True)
+    # the new cache entries of the sampled requests (layer 0: same inputs on both sides)
+    for i, b in enumerate(sample):
+        L = int(case.lengths[b])
+        kd, vd = case.ver.kv_read(b, 0, L, 1 + int(acc[b]))
+        ko, vo = caches[i].k[0][L:L + 1 + int(acc[b])], caches[i].v[0][L:L + 1 + int(acc[b])]
+        assert np.max(np.abs(kd.float().cpu().numpy() - ko)) < 0.02
+        assert np.mean(kd.float().cpu().numpy() != ko) < 0.01
+        assert np.mean(vd.float().cpu().numpy() != vo) < 0.01
+    case.close()
