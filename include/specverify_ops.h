@@ -21,10 +21,28 @@ extern "C" {
  * throughput at large per-worker batch, Section 3 "Challenge #1"):
  *   out[s][m][n] = sum over k in split s of A[m][k] * W[n][k],   s = 0 .. splits-1
  * A [M,K] bf16, W [N,K] bf16, out [splits,M,N] fp32 (the consumer adds the splits).
- * N % 128 == 0, K % (64*splits) == 0.  variant selects the work-group tile (0: 128x128, 1: 64x128,
- * 2: 256x128 tokens x features). */
+ * N % 128 == 0, K % (64*splits) == 0.  variant selects the kernel and work-group tile (tokens x features):
+ * 0: 128x128, 1: 64x128, 2: 256x128 staged through registers; 3: 160x256, 4: 160x128, 5: 128x256, 6: 128x128
+ * loaded straight into LDS (3 and 5 need N % 256 == 0).  packed != 0: W is in sv_op_pack_weight order
+ * (variants 3..6 only). */
 int sv_op_gemm_bf16(const void *A, const void *W, float *out, int M, int N, int K, int splits, int variant,
-                    void *stream);
+                    int packed, void *stream);
+
+/* The same projection with both operands in packed order, by the weight-streaming kernel: Ap = activations
+ * packed by sv_op_pack_rows, Wp = weights packed by sv_op_pack_weight, out [splits, M, N] fp32.
+ * wide != 0: 256 output features per work-group (N % 256 == 0), else 128.  K % (64*splits) == 0. */
+int sv_op_gemm_bf16_ws(const void *Ap, const void *Wp, float *out, int M, int N, int K, int splits, int wide,
+                       void *stream);
+
+/* Reorder row-major bf16 activations src [M, K] into dst (ceil(M/32)*32*K elements) in the order the
+ * weight-streaming kernel reads them: [ceil(M/32)][K/16][64 lanes][8 elements], lane 32*g + r of a fragment
+ * holding row r of the 32-row tile, elements 8*g .. 8*g+7 of the 16-wide k slice; padding rows are zero. */
+int sv_op_pack_rows(const void *src, void *dst, int M, int K, void *stream);
+
+/* Reorder a row-major bf16 matrix src [N, K] into dst (N*K elements, distinct from src) in the order the
+ * projection kernels stream it: [N/128][K/16][4 tiles of 32 rows][64 lanes][8 elements], where lane 32*g + r
+ * of a tile holds row r, elements 8*g .. 8*g+7 of the 16-wide k slice.  N % 128 == 0, K % 32 == 0. */
+int sv_op_pack_weight(const void *src, void *dst, int N, int K, void *stream);
 
 /* Accept/reject + replacement/bonus draw + chain choice on given target logits (the rule restated at
  * verify_step).  logits fp32 [B*(1+N*k), V] in verify_step's row order; other arguments as in
@@ -56,7 +74,7 @@ int sv_profile_enable(sv_ctx *, unsigned kind_mask);
 int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launches /* host */);
 
 /* Tuning / diagnostic knobs of a context.
- *   SV_OPT_GEMM_VARIANT  work-group tile of the bf16 projections (0..2, default 0)
+ *   SV_OPT_GEMM_VARIANT  kernel / work-group tile of the bf16 projections (0..6; -1 = per shape, default)
  *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)
  *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for
  *   SV_OPT_ATTN_CHUNK_KEYS  keys per split-KV chunk of the bf16 attention (multiple of 1024, default 1024) */

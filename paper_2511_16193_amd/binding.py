@@ -25,7 +25,7 @@ EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_step",
-    "sv_op_gemm_bf16", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
+    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
     "sv_profile_read",
 ]
 
@@ -38,7 +38,8 @@ class SvModel(C.Structure):
 
 class SvWeights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
-               [(n, C.POINTER(C.c_void_p)) for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")]
+               [(n, C.POINTER(C.c_void_p)) for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")] + \
+               [("packed", C.c_int32)]
 
 
 class SvRuntime(C.Structure):
@@ -82,7 +83,11 @@ def load_library() -> C.CDLL:
     lib.verify_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
     lib.verify_step.argtypes = [C.c_void_p, C.POINTER(SvBatch), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(SvOut)]
     lib.sv_op_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
-                                    C.c_void_p]
+                                    C.c_int, C.c_void_p]
+    lib.sv_op_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    lib.sv_op_pack_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    lib.sv_op_gemm_bf16_ws.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                       C.c_void_p]
     lib.sv_op_sample_scratch_bytes.restype = C.c_size_t
     lib.sv_op_sample_scratch_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     lib.sv_op_sample.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 5
@@ -125,7 +130,7 @@ class Verifier:
     def __init__(self, model: dict, weights: dict, *, max_batch: int, max_k: int, max_chains: int = 1,
                  max_seqs: int | None = None, page_size: int = 64, num_pages: int, max_pages_per_seq: int,
                  verify_mode: int = SV_STOCHASTIC, sample_mode: int = SV_EXP_RACE, temperature: float = 1.0,
-                 device="cuda:0"):
+                 packed: bool = False, device="cuda:0"):
         self.lib = lib()
         self.device = torch.device(device)
         self.model = dict(model)
@@ -161,7 +166,7 @@ class Verifier:
         self._arrs = {n: arr(n) for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")}
         w = SvWeights(weights["embed"].data_ptr(), weights["lm_head"].data_ptr(), weights["final_norm"].data_ptr(),
                       *[self._arrs[n] if self._arrs[n] is not None else None
-                        for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")])
+                        for n in ("ln1", "wqkv", "wo", "ln2", "w_gate_up", "w_down", "w_router")], 1 if packed else 0)
         ctx = C.c_void_p()
         with torch.cuda.device(self.device):
             rc = self.lib.verify_init(C.byref(self.m), C.byref(w), C.byref(self.rt), _stream_ptr(), C.byref(ctx))
@@ -281,13 +286,57 @@ class Verifier:
 
 # ---- single operations ----
 
-def op_gemm_bf16(a: torch.Tensor, w: torch.Tensor, splits: int = 1, variant: int = 0) -> torch.Tensor:
-    """a [M,K] bf16, w [N,K] bf16 -> [splits, M, N] fp32 partial products."""
+def op_pack_weight(w: torch.Tensor) -> torch.Tensor:
+    """Row-major bf16 [N,K] (or a stack [E,N,K]) -> same shape, fragment order of the projection kernels."""
+    assert w.dtype == torch.bfloat16 and w.is_contiguous() and w.is_cuda
+    out = torch.empty_like(w)
+    mats = w.reshape(-1, w.shape[-2], w.shape[-1])
+    outs = out.reshape(-1, w.shape[-2], w.shape[-1])
+    for i in range(mats.shape[0]):
+        rc = lib().sv_op_pack_weight(_ptr(mats[i]), _ptr(outs[i]), w.shape[-2], w.shape[-1], _stream_ptr())
+        if rc != 0:
+            raise SvError(rc, "sv_op_pack_weight")
+    return out
+
+
+def op_pack_rows(a: torch.Tensor) -> torch.Tensor:
+    """Row-major bf16 activations [M,K] -> packed order, ceil(M/32)*32 rows (padding rows zero)."""
+    assert a.dtype == torch.bfloat16 and a.is_contiguous() and a.is_cuda
+    M, K = a.shape
+    out = torch.empty(((M + 31) // 32 * 32, K), dtype=torch.bfloat16, device=a.device)
+    rc = lib().sv_op_pack_rows(_ptr(a), _ptr(out), M, K, _stream_ptr())
+    if rc != 0:
+        raise SvError(rc, "sv_op_pack_rows")
+    return out
+
+
+def op_gemm_bf16_ws(a_packed: torch.Tensor, w_packed: torch.Tensor, M: int, splits: int = 1, wide: bool = True) -> torch.Tensor:
+    """Weight-streaming projection on packed operands -> [splits, M, N] fp32 partial products."""
+    K = a_packed.shape[1]
+    N = w_packed.shape[0]
+    out = torch.empty((splits, M, N), dtype=torch.float32, device=a_packed.device)
+    rc = lib().sv_op_gemm_bf16_ws(_ptr(a_packed), _ptr(w_packed), _ptr(out), M, N, K, splits, 1 if wide else 0, _stream_ptr())
+    if rc != 0:
+        raise SvError(rc, "sv_op_gemm_bf16_ws")
+    return out
+
+
+def pack_weights(weights: dict) -> dict:
+    """Packed copies of the projection matrices of a weight dict (embed and gains shared)."""
+    names = ("wqkv", "wo", "w_gate_up", "w_down")
+    out = {k: v for k, v in weights.items() if k != "layers"}
+    out["lm_head"] = op_pack_weight(weights["lm_head"])
+    out["layers"] = [{k: (op_pack_weight(v) if k in names else v) for k, v in lw.items()} for lw in weights["layers"]]
+    return out
+
+
+def op_gemm_bf16(a: torch.Tensor, w: torch.Tensor, splits: int = 1, variant: int = 0, packed: bool = False) -> torch.Tensor:
+    """a [M,K] bf16, w [N,K] bf16 (row-major, or packed with packed=True) -> [splits, M, N] fp32 partial products."""
     assert a.dtype == torch.bfloat16 and w.dtype == torch.bfloat16 and a.is_contiguous() and w.is_contiguous()
     M, K = a.shape
     N = w.shape[0]
     out = torch.empty((splits, M, N), dtype=torch.float32, device=a.device)
-    rc = lib().sv_op_gemm_bf16(_ptr(a), _ptr(w), _ptr(out), M, N, K, splits, variant, _stream_ptr())
+    rc = lib().sv_op_gemm_bf16(_ptr(a), _ptr(w), _ptr(out), M, N, K, splits, variant, 1 if packed else 0, _stream_ptr())
     if rc != 0:
         raise SvError(rc, "sv_op_gemm_bf16")
     return out

@@ -293,7 +293,7 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, int rows_pad
         den += f * a.part_ml[pr * 2 + 1];
         num += f * a.part_o[pr * HD + d];
     }
-    reinterpret_cast<bf16_t*>(a.out)[((int64_t)t * a.Hq + h) * HD + d] = f2bf(num / den);
+    reinterpret_cast<bf16_t*>(a.out)[act_index(t, h * HD + d, a.Hq * HD, a.out_packed)] = f2bf(num / den);
 }
 
 // Generic path: one wave per (new row, q head).  Lane-strided keys, per-lane online softmax with the
@@ -331,11 +331,11 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnArgs a, float scal
     const float M = wave_max(m);
     const float f = m == -INFINITY ? 0.f : expf(m - M);
     const float den = wave_sum(l * f);
-    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)t * a.Hq + h) * D;
+    T* out = reinterpret_cast<T*>(a.out);
 #pragma unroll
     for (int d = 0; d < D; ++d) {
         const float v = wave_sum(acc[d] * f);
-        if (lane == 0) Store<T>::store(out + d, v / den);
+        if (lane == 0) Store<T>::store(out + act_index(t, h * D + d, a.Hq * D, a.out_packed), v / den);
     }
 }
 

@@ -65,6 +65,14 @@ __host__ __device__ __forceinline__ int64_t kv_v_index(const KvGeom& g, int laye
            ((ht * 64) + grp * 16 + r) * 8 + j;
 }
 
+// Activations that feed a projection, [rows, K]: row-major, or (packed) in the fragment order the
+// weight-streaming kernel reads -- [rows/32][K/16][64 lanes][8], lane 32*g + r of a fragment holding row r of
+// the 32-row tile, elements 8*g .. 8*g+7 of the 16-wide slice.
+__host__ __device__ __forceinline__ int64_t act_index(int row, int col, int K, bool packed) {
+    if (!packed) return (int64_t)row * K + col;
+    return ((((int64_t)(row >> 5) * (K >> 4) + (col >> 4)) * 64) + ((col >> 3) & 1) * 32 + (row & 31)) * 8 + (col & 7);
+}
+
 // Index of new row j (0 = x0, then chain 0's drafts, chain 1's ...) -> chain, index in chain.
 __host__ __device__ __forceinline__ int row_chain(int j, int k) { return j == 0 ? -1 : (j - 1) / k; }
 __host__ __device__ __forceinline__ int row_index_in_chain(int j, int k) { return j == 0 ? 0 : (j - 1) % k + 1; }

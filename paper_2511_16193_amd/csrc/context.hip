@@ -69,9 +69,10 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.rope = take(sizeof(float) * (size_t)T * m.head_dim);
     L.row_stat = take(sizeof(float) * 4 * T);
     L.h = take(sizeof(float) * (size_t)T * m.d_model);
-    L.a_norm = take(es * (size_t)T * m.d_model);
+    const size_t Tp = (size_t)(T + 31) / 32 * 32;          // packed activations come in 32-row tiles
+    L.a_norm = take(es * Tp * m.d_model);
     L.q = take(es * (size_t)T * qw);
-    L.attn = take(es * (size_t)T * qw);
+    L.attn = take(es * Tp * qw);
     // split-K partial products: the largest splits * rows * features any projection can ask for
     size_t part = 0;
     const int shapes[4][2] = {{qkvw, m.d_model}, {m.d_model, qw}, {2 * F, m.d_model}, {m.d_model, F}};
@@ -81,7 +82,7 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
             part = std::max(part, (size_t)(m.dtype == SV_BF16 ? pick_splits(M, sh[0], sh[1]) : 1) * M * sh[0]);
     }
     L.part = take(sizeof(float) * part);
-    L.act = take(es * (size_t)T * F);
+    L.act = take(es * Tp * F);
     L.logits = take(sizeof(float) * (size_t)T * m.vocab);
     const int G = m.n_q_heads / std::max(1, m.n_kv_heads);
     L.rows_pad = 64;
@@ -126,7 +127,8 @@ struct sv_ctx {
     bool staged_valid[kRing];
     int ring_pos;
     int n_work;                                           // attention work items staged for the current batch
-    int gemm_variant;
+    int gemm_variant;                                     // -1 = choose per shape
+    bool packed;                                          // projection weights are in fragment order
     bool attn_generic;
     int attn_min_rt;
     int attn_chunk;                                       // keys per split-KV chunk (multiple of kChunkKeys)
@@ -217,6 +219,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     if (!w->embed || !w->lm_head || !w->final_norm || !w->ln1 || !w->wqkv || !w->wo || !w->ln2 || !w->w_gate_up || !w->w_down)
         return SV_EINVAL;
     if (m->n_experts > 0) return SV_EUNSUPPORTED;                 // mixture-of-experts FFN: not built yet
+    if (w->packed && m->dtype != SV_BF16) return SV_EINVAL;        // only bf16 projections have a packed form
     if (m->head_dim != 64 && m->head_dim != 128) return SV_EUNSUPPORTED;
     if (m->d_model % 4 != 0 || m->d_model > 8192) return SV_EUNSUPPORTED;   // RMSNorm kernel: float4 pieces, <= 8 per thread
     if (m->dtype == SV_BF16) {
@@ -247,7 +250,8 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->free_pages.resize(r->num_pages);
     for (int i = 0; i < r->num_pages; ++i) c->free_pages[i] = r->num_pages - 1 - i;   // pop_back yields 0,1,2..
     c->ring_pos = 0;
-    c->gemm_variant = 0;
+    c->gemm_variant = -1;
+    c->packed = w->packed != 0;
     c->attn_generic = false;
     c->attn_min_rt = 1;
     c->attn_chunk = kChunkKeys;
@@ -431,12 +435,29 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
     return SV_OK;
 }
 
-static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int N, int K, int* splits_out) {
+// Work-group tile for a projection of M rows onto N features: the token extent (128 or 160) that wastes
+// fewer padded rows, 256 features wide when that still leaves enough work-groups.
+static int pick_variant(const sv_ctx* c, int M, int N) {
+    if (c->gemm_variant >= 0) return c->gemm_variant;
+    const int w128 = (M + 127) / 128 * 128, w160 = (M + 159) / 160 * 160;
+    const bool m160 = w160 < w128;
+    const bool wide = N % 256 == 0 && (N / 256) * ((M + (m160 ? 159 : 127)) / (m160 ? 160 : 128)) >= 256;
+    return m160 ? (wide ? 3 : 4) : (wide ? 5 : 6);
+}
+
+static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int N, int K, int* splits_out, bool allow_split = true) {
     ProfScope prof(c, SV_PROF_GEMM);
     if (c->model.dtype == SV_BF16) {
-        const int s = pick_splits(M, N, K);
+        const int s = allow_split ? pick_splits(M, N, K) : 1;
         *splits_out = s;
-        SV_HIP(c, gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, c->gemm_variant, c->stream));
+        if (c->packed) {
+            // packed weights + packed activations: the weight-streaming kernel; 128-feature strips (two
+            // work-groups per CU) unless the projection is wide enough to fill the chip many times over
+            const bool wide = N % 256 == 0 && (int64_t)(N / 128) * ((M + 159) / 160) * s >= 2048;
+            SV_HIP(c, gemm_bf16_ws((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, wide, c->stream));
+        } else {
+            SV_HIP(c, gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, pick_variant(c, M, N), false, c->stream));
+        }
     } else {
         *splits_out = 1;
         SV_HIP(c, gemm_f32((const float*)A, (const float*)W, out, M, N, K, c->stream));
@@ -465,7 +486,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
 
     int pending = 0;      // split-K partials of the previous projection, still to be added to h
     for (int l = 0; l < m.n_layers; ++l) {
-        SV_HIP(c, add_rmsnorm(h, part, pending, c->ln1[l], a_norm, m.dtype, T, d, m.rms_eps, st));
+        SV_HIP(c, add_rmsnorm(h, part, pending, c->ln1[l], a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
         int s_qkv = 1;
         SV_TRY(gemm(c, a_norm, c->wqkv[l], part, T, qkvw, d, &s_qkv));
         RopeAppend ra;
@@ -482,6 +503,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml);
         aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
         aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work;
+        aa.out_packed = c->packed;
         aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
         aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
         {
@@ -491,21 +513,15 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
 
         int s_o = 1;
         SV_TRY(gemm(c, aa.out, c->wo[l], part, T, d, qw, &s_o));
-        SV_HIP(c, add_rmsnorm(h, part, s_o, c->ln2[l], a_norm, m.dtype, T, d, m.rms_eps, st));
+        SV_HIP(c, add_rmsnorm(h, part, s_o, c->ln2[l], a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
         int s_gu = 1;
         SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
-        SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, st));
+        SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, c->packed, st));
         SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
     }
-    SV_HIP(c, add_rmsnorm(h, part, pending, c->final_norm, a_norm, m.dtype, T, d, m.rms_eps, st));
-    {
-        ProfScope prof(c, SV_PROF_GEMM);
-        if (m.dtype == SV_BF16)
-            SV_HIP(c, gemm_bf16((const bf16_t*)a_norm, (const bf16_t*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, 1,
-                                c->gemm_variant, st));
-        else
-            SV_HIP(c, gemm_f32((const float*)a_norm, (const float*)c->lm_head, c->at<float>(L.logits), T, m.vocab, d, st));
-    }
+    SV_HIP(c, add_rmsnorm(h, part, pending, c->final_norm, a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
+    int one = 1;
+    SV_TRY(gemm(c, a_norm, c->lm_head, c->at<float>(L.logits), T, m.vocab, d, &one, false));
     return SV_OK;
 }
 
@@ -579,10 +595,31 @@ extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts,
 // -------------------------------------------------- single-operation entry points ---
 
 extern "C" int sv_op_gemm_bf16(const void* A, const void* W, float* out, int M, int N, int K, int splits, int variant,
-                               void* stream) {
-    if (!A || !W || !out || M <= 0 || !gemm_bf16_shape_ok(N, K, splits)) return SV_EINVAL;
-    return gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, splits, variant, (hipStream_t)stream) == hipSuccess
+                               int packed, void* stream) {
+    if (!A || !W || !out || M <= 0 || !gemm_bf16_shape_ok(N, K, splits) || !gemm_bf16_variant_ok(variant, N) ||
+        (packed && variant < 3))
+        return SV_EINVAL;
+    return gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, splits, variant, packed != 0, (hipStream_t)stream) ==
+                   hipSuccess ? SV_OK : SV_EHIP;
+}
+
+extern "C" int sv_op_gemm_bf16_ws(const void* Ap, const void* Wp, float* out, int M, int N, int K, int splits, int wide,
+                                  void* stream) {
+    if (!Ap || !Wp || !out || M <= 0 || N <= 0 || K <= 0 || splits <= 0 || N % (wide ? 256 : 128) != 0 ||
+        K % (64 * splits) != 0)
+        return SV_EINVAL;
+    return gemm_bf16_ws((const bf16_t*)Ap, (const bf16_t*)Wp, out, M, N, K, splits, wide != 0, (hipStream_t)stream) == hipSuccess
                ? SV_OK : SV_EHIP;
+}
+
+extern "C" int sv_op_pack_rows(const void* src, void* dst, int M, int K, void* stream) {
+    if (!src || !dst || src == dst || M <= 0 || K <= 0 || K % 16 != 0) return SV_EINVAL;
+    return pack_rows((const bf16_t*)src, (bf16_t*)dst, M, K, (hipStream_t)stream) == hipSuccess ? SV_OK : SV_EHIP;
+}
+
+extern "C" int sv_op_pack_weight(const void* src, void* dst, int N, int K, void* stream) {
+    if (!src || !dst || src == dst || N <= 0 || K <= 0 || N % 128 != 0 || K % 32 != 0) return SV_EINVAL;
+    return pack_weight((const bf16_t*)src, (bf16_t*)dst, N, K, (hipStream_t)stream) == hipSuccess ? SV_OK : SV_EHIP;
 }
 
 extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const float* draft_probs, const float* uniforms,
@@ -626,6 +663,7 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.part_o = c->at<float>(c->lay.part_o); aa.part_ml = c->at<float>(c->lay.part_ml);
     aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
     aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(c->lay.work); aa.n_work = c->n_work;
+    aa.out_packed = false;
     aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
     SV_HIP(c, attention(aa, c->stream));
@@ -684,7 +722,8 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
     if (!c) return SV_EINVAL;
     switch (option) {
         case SV_OPT_GEMM_VARIANT:
-            if (value < 0 || value > 2) return c->fail(SV_EINVAL, "gemm variant %d", value);
+            if (value < -1 || value > 6)
+                return c->fail(SV_EINVAL, "gemm variant %d", value);
             c->gemm_variant = value;
             return SV_OK;
         case SV_OPT_ATTN_GENERIC:

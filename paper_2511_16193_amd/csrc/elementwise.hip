@@ -41,7 +41,7 @@ __global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restr
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int S,
                                                           int64_t part_stride, const T* __restrict__ w,
-                                                          T* __restrict__ a, int d, float eps) {
+                                                          T* __restrict__ a, int d, float eps, bool packed) {
     __shared__ float red[4];
     const int t = blockIdx.x;
     const int nq = d >> 2;                               // float4 pieces per row
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
         if (i < nq) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                Store<T>::store(a + (int64_t)t * d + 4 * i + e, x[v][e] * r * Store<T>::load(w + 4 * i + e));
+                Store<T>::store(a + act_index(t, 4 * i + e, d, packed), x[v][e] * r * Store<T>::load(w + 4 * i + e));
         }
     }
 }
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64) void rope_append_kernel(RopeAppend p) {
 
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ part, int S, int64_t stride,
-                                                     T* __restrict__ act, int F) {
+                                                     T* __restrict__ act, int F, bool packed) {
     const int t = blockIdx.y;
     const int f = blockIdx.x * 256 + threadIdx.x;
     if (f >= F) return;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ p
         u += src[s * stride + F + f];
     }
     const float y = g / (1.0f + expf(-g)) * u;
-    Store<T>::store(act + (int64_t)t * F + f, y);
+    Store<T>::store(act + act_index(t, f, F, packed), y);
 }
 
 template <typename T>
@@ -186,23 +186,24 @@ hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, floa
 }
 
 template <typename T>
-static hipError_t add_rmsnorm_t(float* h, const float* part, int S, const T* w, T* a, int T_, int d, float eps, hipStream_t st) {
+static hipError_t add_rmsnorm_t(float* h, const float* part, int S, const T* w, T* a, int T_, int d, float eps, bool packed,
+                                hipStream_t st) {
     const int64_t stride = (int64_t)T_ * d;
     const int nq = d / 4;
     if (d % 4 != 0 || nq > 256 * 8) return hipErrorInvalidValue;
     if (nq <= 256 * 2)
-        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 2>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 2>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed);
     else if (nq <= 256 * 4)
-        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 4>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 4>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed);
     else
-        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 8>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 8>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed);
     return hipGetLastError();
 }
 
 hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
-                       hipStream_t st) {
-    if (dtype == 1) return add_rmsnorm_t<bf16_t>(h, part, S, (const bf16_t*)w, (bf16_t*)a, T, d, eps, st);
-    return add_rmsnorm_t<float>(h, part, S, (const float*)w, (float*)a, T, d, eps, st);
+                       bool packed, hipStream_t st) {
+    if (dtype == 1) return add_rmsnorm_t<bf16_t>(h, part, S, (const bf16_t*)w, (bf16_t*)a, T, d, eps, packed, st);
+    return add_rmsnorm_t<float>(h, part, S, (const float*)w, (float*)a, T, d, eps, packed, st);
 }
 
 hipError_t rope_append(const RopeAppend& p, hipStream_t st) {
@@ -214,13 +215,13 @@ hipError_t rope_append(const RopeAppend& p, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t swiglu(const float* gu_part, int S, void* act, int dtype, int T, int F, hipStream_t st) {
+hipError_t swiglu(const float* gu_part, int S, void* act, int dtype, int T, int F, bool packed, hipStream_t st) {
     const int64_t stride = (int64_t)T * 2 * F;
     dim3 grid((F + 255) / 256, T);
     if (dtype == 1)
-        hipLaunchKernelGGL(swiglu_kernel<bf16_t>, grid, dim3(256), 0, st, gu_part, S, stride, (bf16_t*)act, F);
+        hipLaunchKernelGGL(swiglu_kernel<bf16_t>, grid, dim3(256), 0, st, gu_part, S, stride, (bf16_t*)act, F, packed);
     else
-        hipLaunchKernelGGL(swiglu_kernel<float>, grid, dim3(256), 0, st, gu_part, S, stride, (float*)act, F);
+        hipLaunchKernelGGL(swiglu_kernel<float>, grid, dim3(256), 0, st, gu_part, S, stride, (float*)act, F, packed);
     return hipGetLastError();
 }
 

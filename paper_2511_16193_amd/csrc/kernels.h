@@ -8,8 +8,13 @@ namespace sv {
 
 // ---- gemm.hip ----
 int gemm_bf16_shape_ok(int N, int K, int splits);
+int gemm_bf16_variant_ok(int variant, int N);
 hipError_t gemm_bf16(const bf16_t* A, const bf16_t* W, float* out, int M, int N, int K, int splits, int variant,
-                     hipStream_t st);
+                     bool packed, hipStream_t st);
+hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st);
+hipError_t pack_rows(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st);
+hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool wide,
+                        hipStream_t st);
 hipError_t gemm_f32(const float* A, const float* W, float* out, int M, int N, int K, hipStream_t st);
 
 // ---- elementwise.hip ----
@@ -29,7 +34,7 @@ hipError_t prep_rows(const RowPrep& p, hipStream_t st);
 hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, float* h, int T, int d, hipStream_t st);
 // h[t,:] += sum_s part[s][t,:] (S may be 0), then a[t,:] = storage(h * rsqrt(mean(h^2)+eps) * w)
 hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
-                       hipStream_t st);
+                       bool packed, hipStream_t st);
 struct RopeAppend {
     const float* qkv_part; int S;       // [S][T][(Hq+2Hkv)*hd]
     const float* rope;                  // [T][hd/2][2]
@@ -41,7 +46,7 @@ struct RopeAppend {
     int T, n, Hq, Hkv, hd, dtype;
 };
 hipError_t rope_append(const RopeAppend& p, hipStream_t st);
-hipError_t swiglu(const float* gu_part, int S, void* act, int dtype, int T, int F, hipStream_t st);
+hipError_t swiglu(const float* gu_part, int S, void* act, int dtype, int T, int F, bool packed, hipStream_t st);
 hipError_t kv_copy(void* pool, const KvGeom& geom, int layer, const int32_t* page_table_row, int pos0, int n,
                    void* k, void* v, int dtype, bool to_pool, hipStream_t st);
 hipError_t set_i32(int32_t* p, int32_t v, hipStream_t st);
@@ -61,6 +66,7 @@ struct AttnArgs {
     int chunk_keys, max_chunks;
     const int32_t* work; int n_work;    // (request << 16 | chunk) items of the bf16 kernel
     int min_row_tiles;                  // lower bound on the 16-row tiles of the bf16 kernel (tuning)
+    bool out_packed;                    // write `out` in the packed activation order (see act_index)
     bool force_generic;                 // take the untuned one-wave-per-row path whatever the shape
 };
 int attn_rows_pad(int n, int group);        // padded query rows per (request, kv head); 0 = MFMA path not applicable

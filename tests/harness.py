@@ -28,14 +28,16 @@ class Case:
     """One workload instantiated on both sides."""
 
     def __init__(self, shape: W.Shape, lengths, *, verify_mode, sample_mode=OV.SAMPLE_EXP_RACE, temperature=1.0,
-                 page_size=64, extra_tokens=64, synthetic_kv=True, device="cuda:0"):
-        from paper_2511_16193_amd import Verifier
+                 page_size=64, extra_tokens=64, synthetic_kv=True, packed=False, device="cuda:0"):
+        from paper_2511_16193_amd import Verifier, pack_weights
         self.shape, self.device = shape, device
         self.spec = spec_of(shape)
         self.verify_mode, self.sample_mode, self.temperature = verify_mode, sample_mode, temperature
         w_cpu = W.make_weights(shape, "cpu")
         self.wn = W.weights_to_numpy(w_cpu)
         self.wd = to_device(w_cpu, device)
+        if packed:                                   # projection weights in the library's streaming order
+            self.wd = pack_weights(self.wd)
         self.lengths = np.asarray(lengths, dtype=np.int64)
         B = len(self.lengths)
         n = 1 + shape.n_chains * shape.k
@@ -43,7 +45,8 @@ class Case:
         pps = (cap + page_size - 1) // page_size + 1
         self.ver = Verifier(shape.model_fields(), self.wd, max_batch=B, max_k=shape.k, max_chains=shape.n_chains,
                             max_seqs=B, page_size=page_size, num_pages=B * pps + 2, max_pages_per_seq=pps,
-                            verify_mode=verify_mode, sample_mode=sample_mode, temperature=temperature, device=device)
+                            verify_mode=verify_mode, sample_mode=sample_mode, temperature=temperature, packed=packed,
+                            device=device)
         self.caches = [M.SeqCache(self.spec, cap) for _ in range(B)]
         for b in range(B):
             L = int(self.lengths[b])

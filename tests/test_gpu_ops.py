@@ -16,20 +16,41 @@ def bf16_cpu(shape, std, seed):
     return (torch.randn(shape, generator=g) * std).to(torch.bfloat16)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("M_,N,K,splits", [(320, 512, 1024, 1), (37, 256, 512, 4), (129, 128, 64, 1), (1, 384, 2048, 8),
-                                           (700, 640, 448, 1)])
+                                           (700, 640, 448, 1), (321, 768, 3584, 2), (320, 1024, 192, 1)])
 def test_gemm_bf16_matches_float64_product(variant, M_, N, K, splits):
     """Several tiles plus a ragged last row tile; every split count; the reduction in float64 on the
     same bf16 inputs is the reference.  fp32 accumulation of K <= 2048 products of magnitude ~0.02:
     absolute error far below 1e-4."""
-    from paper_2511_16193_amd import op_gemm_bf16
-    if K % (64 * splits):
-        pytest.skip("K not divisible")
+    from paper_2511_16193_amd import op_gemm_bf16, op_pack_weight
+    if K % (64 * splits) or (variant in (3, 5) and N % 256):
+        pytest.skip("shape not covered by this tile")
     a = bf16_cpu((M_, K), 1.0, 1)
     w = bf16_cpu((N, K), 0.02, 2)
     want = M.matmul_wt(a.float().numpy().astype(np.float64), w.float().numpy())
-    got = op_gemm_bf16(a.to(DEV), w.to(DEV), splits=splits, variant=variant)
+    for packed in ([False, True] if variant >= 3 else [False]):
+        wd = w.to(DEV)
+        if packed:                      # weights reordered into the streaming order of the direct-to-LDS kernel
+            wd = op_pack_weight(wd)
+        got = op_gemm_bf16(a.to(DEV), wd, splits=splits, variant=variant, packed=packed)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy().astype(np.float64).sum(axis=0)
+        assert np.max(np.abs(got - want)) < 1e-4, packed
+
+
+@pytest.mark.parametrize("M_,N,K,splits,wide", [(320, 512, 1024, 1, True), (37, 256, 512, 4, True), (129, 128, 64, 1, False),
+                                               (1, 384, 2048, 8, False), (700, 640, 448, 1, False),
+                                               (321, 768, 3584, 2, True), (320, 1024, 192, 1, True),
+                                               (64, 256, 2368, 1, True)])
+def test_gemm_weight_streaming_matches_float64_product(M_, N, K, splits, wide):
+    """The weight-streaming kernel on packed operands: ragged row tiles (rows beyond M read as the last
+    tile), both strip widths, fills of 8 and of 4 k-slices, every split count."""
+    from paper_2511_16193_amd import op_gemm_bf16_ws, op_pack_weight, op_pack_rows
+    a = bf16_cpu((M_, K), 1.0, 1)
+    w = bf16_cpu((N, K), 0.02, 2)
+    want = M.matmul_wt(a.float().numpy().astype(np.float64), w.float().numpy())
+    got = op_gemm_bf16_ws(op_pack_rows(a.to(DEV)), op_pack_weight(w.to(DEV)), M_, splits=splits, wide=wide)
     torch.cuda.synchronize()
     got = got.cpu().numpy().astype(np.float64).sum(axis=0)
     assert np.max(np.abs(got - want)) < 1e-4

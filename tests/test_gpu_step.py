@@ -62,25 +62,30 @@ def test_cfg1_tiny_fp32_greedy_chained_steps():
 SMALL_BF16 = W.Shape("small-bf16", 3, 256, 8, 2, 128, 512, 2048, dtype="bf16", batch=5, k=4, seed=77)
 
 
-@pytest.mark.parametrize("k,n_chains,vmode,smode", [
-    (4, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE),
-    (4, 1, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF),
-    (1, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE),
-    (8, 1, OV.GREEDY, 0),
-    (0, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE),
-    (3, 3, OV.GREEDY, 0),
-    (3, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE),
+@pytest.mark.parametrize("k,n_chains,vmode,smode,packed", [
+    (4, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, False),
+    (4, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),
+    (4, 1, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, True),
+    (1, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),
+    (8, 1, OV.GREEDY, 0, False),
+    (8, 1, OV.GREEDY, 0, True),
+    (0, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),
+    (3, 3, OV.GREEDY, 0, True),
+    (3, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, False),
+    (3, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),
 ])
-def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode):
+def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed):
     """bf16 decoder small enough for the oracle (3 layers, d 256, 8 q / 2 kv heads x 128, vocab 2048) over a
     synthetic cache whose lengths are ragged and span several split-KV chunks and a partial tile
     (0, 31, 1024, 2500, 4133 entries), so the MFMA attention's tiling, masking and chunk merge are all hit.
+    packed: projection weights (and with them the activations between kernels) in the library's
+    streaming order, which selects the weight-streaming projection kernel.
     Drafts come from target-independent q (about half are accepted because random-weight targets are nearly
     flat).  Two consecutive steps: the second runs on the rolled-back cache."""
     shape = W.scaled_down(SMALL_BF16, k=k, n_chains=n_chains)
     lengths = [0, 31, 1024, 2500, 4133]
     B, V = len(lengths), shape.vocab
-    case = Case(shape, lengths, verify_mode=vmode, sample_mode=smode)
+    case = Case(shape, lengths, verify_mode=vmode, sample_mode=smode, packed=packed)
     x0 = W.make_tokens((B,), V, shape.seed, "x0")
     alive = np.ones(B, dtype=bool)
     accepted = 0

@@ -21,8 +21,8 @@ from . import synth
 
 class DeviceCase:
     def __init__(self, shape: Shape, *, k: int | None = None, n_chains: int | None = None, page_size: int = 64,
-                 verify_mode: int | None = None, sample_mode: int = 1, device="cuda:0", log=None):
-        from paper_2511_16193_amd import Verifier
+                 verify_mode: int | None = None, sample_mode: int = 1, packed: bool = True, device="cuda:0", log=None):
+        from paper_2511_16193_amd import Verifier, pack_weights
         self.shape, self.device = shape, torch.device(device)
         self.k = shape.k if k is None else k
         self.N = shape.n_chains if n_chains is None else n_chains
@@ -33,8 +33,11 @@ class DeviceCase:
         headroom = n + self.k + 2
         pages = [int((L + headroom + page_size - 1) // page_size) for L in self.lengths]
         self.log(f"weights for {shape.name} ...")
-        self.weights = synth.make_weights(shape, self.device)
-        self.ver = Verifier(shape.model_fields(), self.weights, max_batch=self.B, max_k=max(self.k, 1),
+        self.weights = synth.make_weights(shape, self.device)           # row-major (what the oracle reads)
+        # the library streams the projection matrices in its packed order (a one-off device-side reorder)
+        self.weights_dev = pack_weights(self.weights) if packed and shape.dtype == "bf16" else self.weights
+        self.ver = Verifier(shape.model_fields(), self.weights_dev, packed=self.weights_dev is not self.weights,
+                            max_batch=self.B, max_k=max(self.k, 1),
                             max_chains=self.N, max_seqs=self.B, page_size=page_size, num_pages=sum(pages) + 4,
                             max_pages_per_seq=max(pages) + 1,
                             verify_mode=shape.verify_mode if verify_mode is None else verify_mode,
