@@ -96,6 +96,10 @@ def main():
     ap.add_argument("--drafts", choices=["noisy-target", "independent"], default="noisy-target",
                     help="independent: drafts from q = softmax(N(0,1)) without any device decoding step, so that "
                          "every kernel launch of the process has the timed step's shape (used for profiles)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed steps run one plain elementwise pass that reads 1 GiB and writes 1 GiB "
+                         "(torch.neg(src, out=dst) on fp32, an op nothing else in the run uses), the known-size kernel against which the HBM byte "
+                         "counters of a profiler run are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the verification step on ONE GPU (requests shard across workers "
@@ -172,6 +176,14 @@ def main():
                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": attn_gbs / PEAK_HBM_GBS, "traffic": None,
                  "avg_launch_ms": attn_ms / attn_n, "launches_per_step": attn_n // args.steps}
     dominant, other = (roof_gemm, roof_attn) if gemm_ms >= attn_ms else (roof_attn, roof_gemm)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=case.device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.neg(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if args.cpu_seqs > 0:

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 #include <algorithm>
+#include <cmath>
 #include <string>
 #include <vector>
 
@@ -18,6 +19,7 @@ namespace {
 
 constexpr int kRing = 8;              // pinned staging slots for per-step host -> device metadata
 constexpr int kMaxSplits = 8;
+constexpr int kMaxSplitsWs = 16;       // weight-streaming kernel: any divisor of the slice count up to this
 constexpr int kChunkKeys = 1024;      // keys per split-KV chunk of the bf16 attention
 
 struct SeqState {
@@ -34,6 +36,35 @@ int pick_splits(int M, int N, int K) {
     int s = 1;
     while (s < kMaxSplits && tiles * s < 512 && K % (64 * s * 2) == 0) s *= 2;
     return s;
+}
+
+// Launch plan of the weight-streaming projection kernel: reduction splits and strip width, by an estimate of
+// the run time in microseconds.  Constants measured on MI355X: alone on its CU a 128-feature work-group advances
+// one 16-wide slice in 0.125 and a 256-feature one in 0.2; with every CU busy the chip sustains about 0.78 resp.
+// 0.9 PFLOP/s on random data (it is power-limited well below the MFMA peak), which bounds the advance of n
+// concurrent work-groups; 512 resp. 256 work-groups are resident at a time; a partial plane costs its bytes
+// at 3.5 TB/s (written here, read again by the consumer).
+struct WsPlan { int splits; bool wide; };
+WsPlan plan_ws(int M, int N, int K, bool allow_split) {
+    const int tiles_m = (M + 159) / 160, slices = K / 16;
+    WsPlan best{1, false};
+    double best_t = 1e30;
+    for (int wide = 0; wide < 2; ++wide) {
+        if (wide && N % 256 != 0) continue;
+        const double iso = wide ? 0.2 : 0.125, rate = wide ? 0.9e9 : 0.78e9;      // flop per microsecond
+        const double work = 2.0 * 160 * (wide ? 256 : 128) * 16;                  // flop per work-group slice
+        const int cap = wide ? 256 : 512;
+        auto slice_time = [&](int n) { return std::max(iso, n * work / rate); };
+        for (int s = 1; s <= (allow_split ? kMaxSplitsWs : 1); ++s) {
+            if (slices % (4 * s) != 0) continue;
+            const int blocks = (N / (wide ? 256 : 128)) * tiles_m * s;
+            const int full = blocks / cap, rem = blocks % cap;
+            double t = (double)full * (slices / s) * slice_time(cap) + (rem ? (slices / s) * slice_time(rem) : 0.0);
+            if (s > 1) t += (double)s * M * N * 4.0 / 3.5e6;
+            if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0}; }
+        }
+    }
+    return best;
 }
 
 struct Layout {                       // byte offsets into the workspace
@@ -81,6 +112,12 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
         for (auto& sh : shapes)
             part = std::max(part, (size_t)(m.dtype == SV_BF16 ? pick_splits(M, sh[0], sh[1]) : 1) * M * sh[0]);
     }
+    if (m.dtype == SV_BF16)                                 // the same for the plans of the weight-streaming kernel
+        for (int tm = 1; tm <= (T + 159) / 160; ++tm) {
+            const int M = std::min(tm * 160, T);
+            for (auto& sh : shapes)
+                if (sh[1] % 64 == 0) part = std::max(part, (size_t)plan_ws(M, sh[0], sh[1], true).splits * M * sh[0]);
+        }
     L.part = take(sizeof(float) * part);
     L.act = take(es * Tp * F);
     L.logits = take(sizeof(float) * (size_t)T * m.vocab);
@@ -448,14 +485,14 @@ static int pick_variant(const sv_ctx* c, int M, int N) {
 static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int N, int K, int* splits_out, bool allow_split = true) {
     ProfScope prof(c, SV_PROF_GEMM);
     if (c->model.dtype == SV_BF16) {
-        const int s = allow_split ? pick_splits(M, N, K) : 1;
-        *splits_out = s;
         if (c->packed) {
-            // packed weights + packed activations: the weight-streaming kernel; 128-feature strips (two
-            // work-groups per CU) unless the projection is wide enough to fill the chip many times over
-            const bool wide = N % 256 == 0 && (int64_t)(N / 128) * ((M + 159) / 160) * s >= 2048;
-            SV_HIP(c, gemm_bf16_ws((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, wide, c->stream));
+            // packed weights + packed activations: the weight-streaming kernel
+            const WsPlan p = plan_ws(M, N, K, allow_split);
+            *splits_out = p.splits;
+            SV_HIP(c, gemm_bf16_ws((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, p.splits, p.wide, c->stream));
         } else {
+            const int s = allow_split ? pick_splits(M, N, K) : 1;
+            *splits_out = s;
             SV_HIP(c, gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, pick_variant(c, M, N), false, c->stream));
         }
     } else {

@@ -362,11 +362,12 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
         // everyone's share of this fill is in LDS; the other buffer has no reader left
         __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0): own LDS writes done
         __builtin_amdgcn_s_barrier();
-        const bool more = fill + 1 < nfill;
-        if (more) {
+        // next fill's activations: loaded unconditionally (the last fill is loaded twice) so that the loop body
+        // has no branch and the compiler can count the loads in flight exactly; behind a branch it falls back
+        // to waiting for these loads at the first product of the fill
+        const int nxt = fill + 1 < nfill ? fill + 1 : fill;
 #pragma unroll
-            for (int i = 0; i < APW; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + (int64_t)(fill + 1) * KA * 512);
-        }
+        for (int i = 0; i < APW; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + (int64_t)nxt * KA * 512);
         const unsigned char* ab = abuf[fill & 1] + lane * 16;
         static_assert(KA % PD == 0, "ring slots must be static across a fill");
         bf16x8 af[2][MT];                                  // activation fragments: this slice and the next
@@ -375,14 +376,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
 #pragma unroll
         for (int s = 0; s < KA; ++s) {
             const int slice = fill * KA + s;
-            bf16x8 wf[NT];
-#pragma unroll
-            for (int i = 0; i < NT; ++i) wf[i] = __builtin_bit_cast(bf16x8, wring[s % PD][i]);
-            // refill the ring slot just consumed with the slice PD ahead (clamped at the end: a harmless re-load)
-            const int ahead = slice + PD < total_slices ? slice + PD : total_slices - 1;
-#pragma unroll
-            for (int i = 0; i < NT; ++i)
-                wring[s % PD][i] = *reinterpret_cast<const u32x4*>(w_src[i] + (int64_t)ahead * W_STEP);
             if (s + 1 < KA) {
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
@@ -395,14 +388,22 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
             for (int i = 0; i < NT; ++i)
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], af[s & 1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wring[s % PD][i]),
+                                                                        af[s & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            // refill the ring slot just consumed with the slice PD ahead (clamped at the end: a harmless
+            // re-load).  Issued after the products that read the slot, so the slot's registers are dead and
+            // the load lands in place: issued before them, every slot needs a copy, and the compiler
+            // gathers those copies at the top of the fill, behind a wait for the whole ring.
+            const int ahead = slice + PD < total_slices ? slice + PD : total_slices - 1;
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+                wring[s % PD][i] = *reinterpret_cast<const u32x4*>(w_src[i] + (int64_t)ahead * W_STEP);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
 #pragma unroll
-            for (int i = 0; i < APW; ++i)
-                *reinterpret_cast<u32x4*>(&abuf[(fill + 1) & 1][(wave * APW + i) * 1024 + lane * 16]) = areg[i];
-        }
+        for (int i = 0; i < APW; ++i)
+            *reinterpret_cast<u32x4*>(&abuf[(fill + 1) & 1][(wave * APW + i) * 1024 + lane * 16]) = areg[i];
     }
 
     float* dst = out + (int64_t)sp * M * N;
