@@ -61,6 +61,20 @@ int sv_op_sample(const float *logits, const int32_t *drafts, const float *draft_
  * type).  n = 1 + N*k.  Lengths are not changed. */
 int sv_op_attention(sv_ctx *, const int32_t *seq_ids, int B, int n, int k, int layer, const void *q, void *out);
 
+/* The mixture-of-experts feed-forward on its own (the MoE model the paper evaluates, Section 5.3): softmax
+ * router over E experts, top_k largest probabilities (lowest id among equals), renormalised; per selected
+ * expert (silu(x Wg^T) * (x Wu^T)) Wd^T with the product silu * up rounded to bf16; out[t] = weighted sum.
+ * All pointers device.  a_packed: activations [T, d] bf16 in the order sv_op_pack_rows() writes;
+ * w_router [E, d] bf16 row-major; w_gate_up_packed: the [E, 2F, d] tensor (gate rows, then up rows, per expert)
+ * packed by sv_op_pack_weight() as one (E*2F) x d matrix; w_down_packed: [E, d, F] packed as (E*d) x F.
+ * scratch: sv_op_moe_scratch_bytes() bytes, 256-byte aligned.  out [T, d] fp32; top_ids / top_w [T, top_k]
+ * (optional) receive the routing.  SV_EUNSUPPORTED unless E is a multiple of 64 up to 256 and d, F are
+ * multiples of 128. */
+size_t sv_op_moe_scratch_bytes(int T, int d, int E, int top_k, int F);
+int sv_op_moe_ffn(const void *a_packed, const void *w_router, const void *w_gate_up_packed, const void *w_down_packed,
+                  int T, int d, int E, int top_k, int F, void *scratch, size_t scratch_bytes, float *out,
+                  int32_t *top_ids, float *top_w, void *stream);
+
 /* Set the live lengths of n sequences at once (HOST arrays; same meaning as verify_seq_set_len, one
  * small copy and one launch instead of n).  Used to put a batch back to a saved state between steps. */
 int sv_seq_set_lens(sv_ctx *, const int32_t *seq_ids, const int32_t *lens, int n);
@@ -69,7 +83,7 @@ int sv_seq_set_lens(sv_ctx *, const int32_t *seq_ids, const int32_t *lens, int n
  * launch group of kind k is bracketed by a pair of HIP events on the context's stream.
  * sv_profile_read synchronises the stream, returns the summed elapsed time and the number of
  * bracketed groups of that kind since the last read, and forgets them. */
-enum { SV_PROF_GEMM = 0, SV_PROF_ATTENTION = 1, SV_PROF_SAMPLER = 2, SV_PROF_ROLLBACK = 3, SV_PROF_KINDS = 4 };
+enum { SV_PROF_GEMM = 0, SV_PROF_ATTENTION = 1, SV_PROF_SAMPLER = 2, SV_PROF_ROLLBACK = 3, SV_PROF_MOE = 4, SV_PROF_KINDS = 5 };
 int sv_profile_enable(sv_ctx *, unsigned kind_mask);
 int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launches /* host */);
 

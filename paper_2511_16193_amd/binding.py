@@ -19,13 +19,13 @@ SV_FP32, SV_BF16 = 0, 1
 SV_GREEDY, SV_STOCHASTIC = 0, 1
 SV_INVERSE_CDF, SV_EXP_RACE = 0, 1
 SV_OPT_GEMM_VARIANT, SV_OPT_ATTN_GENERIC, SV_OPT_ATTN_MIN_ROW_TILES, SV_OPT_ATTN_CHUNK_KEYS = 1, 2, 3, 4
-SV_PROF_GEMM, SV_PROF_ATTENTION, SV_PROF_SAMPLER, SV_PROF_ROLLBACK = 0, 1, 2, 3
+SV_PROF_GEMM, SV_PROF_ATTENTION, SV_PROF_SAMPLER, SV_PROF_ROLLBACK, SV_PROF_MOE = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_step",
-    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
+    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
     "sv_profile_read",
 ]
 
@@ -91,6 +91,9 @@ def load_library() -> C.CDLL:
     lib.sv_op_sample_scratch_bytes.restype = C.c_size_t
     lib.sv_op_sample_scratch_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     lib.sv_op_sample.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 5
+    lib.sv_op_moe_scratch_bytes.restype = C.c_size_t
+    lib.sv_op_moe_scratch_bytes.argtypes = [C.c_int] * 5
+    lib.sv_op_moe_ffn.argtypes = [C.c_void_p] * 4 + [C.c_int] * 5 + [C.c_void_p, C.c_size_t] + [C.c_void_p] * 4
     lib.sv_op_attention.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p]
     lib.sv_seq_set_lens.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
@@ -290,10 +293,14 @@ def op_pack_weight(w: torch.Tensor) -> torch.Tensor:
     """Row-major bf16 [N,K] (or a stack [E,N,K]) -> same shape, fragment order of the projection kernels."""
     assert w.dtype == torch.bfloat16 and w.is_contiguous() and w.is_cuda
     out = torch.empty_like(w)
-    mats = w.reshape(-1, w.shape[-2], w.shape[-1])
-    outs = out.reshape(-1, w.shape[-2], w.shape[-1])
+    if w.shape[-2] % 128 == 0:          # whole 128-row panels per matrix: a stack packs as one tall matrix
+        mats = w.reshape(1, -1, w.shape[-1])
+        outs = out.reshape(1, -1, w.shape[-1])
+    else:
+        mats = w.reshape(-1, w.shape[-2], w.shape[-1])
+        outs = out.reshape(-1, w.shape[-2], w.shape[-1])
     for i in range(mats.shape[0]):
-        rc = lib().sv_op_pack_weight(_ptr(mats[i]), _ptr(outs[i]), w.shape[-2], w.shape[-1], _stream_ptr())
+        rc = lib().sv_op_pack_weight(_ptr(mats[i]), _ptr(outs[i]), mats.shape[1], mats.shape[2], _stream_ptr())
         if rc != 0:
             raise SvError(rc, "sv_op_pack_weight")
     return out
@@ -319,6 +326,26 @@ def op_gemm_bf16_ws(a_packed: torch.Tensor, w_packed: torch.Tensor, M: int, spli
     if rc != 0:
         raise SvError(rc, "sv_op_gemm_bf16_ws")
     return out
+
+
+def op_moe_ffn(a: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_down: torch.Tensor, top_k: int):
+    """Mixture-of-experts FFN of bf16 rows a [T,d]; w_router [E,d], w_gate_up [E,2F,d], w_down [E,d,F], all bf16
+    row-major (packed here).  -> (out [T,d] fp32, expert ids [T,top_k] int32, weights [T,top_k] fp32)."""
+    T, d = a.shape
+    E, F = w_router.shape[0], w_down.shape[2]
+    ap, gp, dp = op_pack_rows(a), op_pack_weight(w_gate_up), op_pack_weight(w_down)
+    nbytes = lib().sv_op_moe_scratch_bytes(T, d, E, top_k, F)
+    if nbytes == 0:
+        raise SvError(-4, "sv_op_moe_scratch_bytes")
+    scratch = torch.empty(nbytes, dtype=torch.uint8, device=a.device)
+    out = torch.empty((T, d), dtype=torch.float32, device=a.device)
+    ids = torch.empty((T, top_k), dtype=torch.int32, device=a.device)
+    wts = torch.empty((T, top_k), dtype=torch.float32, device=a.device)
+    rc = lib().sv_op_moe_ffn(_ptr(ap), _ptr(w_router.contiguous()), _ptr(gp), _ptr(dp), T, d, E, top_k, F, _ptr(scratch),
+                             nbytes, _ptr(out), _ptr(ids), _ptr(wts), _stream_ptr())
+    if rc != 0:
+        raise SvError(rc, "sv_op_moe_ffn")
+    return out, ids, wts
 
 
 def pack_weights(weights: dict) -> dict:

@@ -70,6 +70,7 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split) {
 struct Layout {                       // byte offsets into the workspace
     size_t seq_len, page_table, batch_seq, upd, work, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
     size_t rope, row_stat, h, a_norm, q, attn, part, act, logits, part_o, part_ml, total;
+    size_t moe_ids, moe_w, moe_cnt, moe_off, moe_perm, moe_inv, moe_act, moe_y;   // mixture-of-experts scratch
     int T, rows_pad, max_chunks;
 };
 
@@ -126,6 +127,18 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     (void)G;
     L.part_o = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * m.head_dim);
     L.part_ml = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * 2);
+    L.moe_ids = L.moe_w = L.moe_cnt = L.moe_off = L.moe_perm = L.moe_inv = L.moe_act = L.moe_y = 0;
+    if (m.n_experts > 0) {
+        const size_t tiles = (size_t)moe_max_tiles(T, m.n_experts, m.top_k);
+        L.moe_ids = take(sizeof(int32_t) * (size_t)T * m.top_k);
+        L.moe_w = take(sizeof(float) * (size_t)T * m.top_k);
+        L.moe_cnt = take(sizeof(int32_t) * m.n_experts);
+        L.moe_off = take(sizeof(int32_t) * (m.n_experts + 1));
+        L.moe_perm = take(sizeof(int32_t) * 32 * tiles);
+        L.moe_inv = take(sizeof(int32_t) * (size_t)T * m.top_k);
+        L.moe_act = take(es * 32 * tiles * m.d_expert);
+        L.moe_y = take(sizeof(float) * 32 * tiles * m.d_model);
+    }
     L.total = o;
     return true;
 }
@@ -255,14 +268,18 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
         return SV_EINVAL;
     if (!w->embed || !w->lm_head || !w->final_norm || !w->ln1 || !w->wqkv || !w->wo || !w->ln2 || !w->w_gate_up || !w->w_down)
         return SV_EINVAL;
-    if (m->n_experts > 0) return SV_EUNSUPPORTED;                 // mixture-of-experts FFN: not built yet
+    if (m->n_experts > 0) {
+        // mixture-of-experts FFN: bf16 with packed weights only, within the expert kernels' shape cover
+        if (m->dtype != SV_BF16 || !w->packed || !w->w_router) return SV_EUNSUPPORTED;
+        if (!moe_shape_ok(L.T, m->d_model, m->n_experts, m->top_k, m->d_expert)) return SV_EUNSUPPORTED;
+    }
     if (w->packed && m->dtype != SV_BF16) return SV_EINVAL;        // only bf16 projections have a packed form
     if (m->head_dim != 64 && m->head_dim != 128) return SV_EUNSUPPORTED;
     if (m->d_model % 4 != 0 || m->d_model > 8192) return SV_EUNSUPPORTED;   // RMSNorm kernel: float4 pieces, <= 8 per thread
     if (m->dtype == SV_BF16) {
         const int qw = m->n_q_heads * m->head_dim, qkvw = (m->n_q_heads + 2 * m->n_kv_heads) * m->head_dim;
         if (!gemm_bf16_shape_ok(qkvw, m->d_model, 1) || !gemm_bf16_shape_ok(m->d_model, qw, 1) ||
-            !gemm_bf16_shape_ok(2 * m->d_ff, m->d_model, 1) || !gemm_bf16_shape_ok(m->d_model, m->d_ff, 1) ||
+            (m->n_experts == 0 && (!gemm_bf16_shape_ok(2 * m->d_ff, m->d_model, 1) || !gemm_bf16_shape_ok(m->d_model, m->d_ff, 1))) ||
             !gemm_bf16_shape_ok(m->vocab, m->d_model, 1))
             return SV_EUNSUPPORTED;                                // GEMM N must be a multiple of 128, K of 64
     }
@@ -275,7 +292,8 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
     c->embed = w->embed; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
     for (int l = 0; l < m->n_layers; ++l) {
-        if (!w->ln1[l] || !w->wqkv[l] || !w->wo[l] || !w->ln2[l] || !w->w_gate_up[l] || !w->w_down[l]) {
+        if (!w->ln1[l] || !w->wqkv[l] || !w->wo[l] || !w->ln2[l] || !w->w_gate_up[l] || !w->w_down[l] ||
+            (m->n_experts > 0 && !w->w_router[l])) {
             delete c;
             return SV_EINVAL;
         }
@@ -551,6 +569,20 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         int s_o = 1;
         SV_TRY(gemm(c, aa.out, c->wo[l], part, T, d, qw, &s_o));
         SV_HIP(c, add_rmsnorm(h, part, s_o, c->ln2[l], a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
+        if (m.n_experts > 0) {
+            MoeArgs ma;
+            ma.a = (const bf16_t*)a_norm; ma.w_router = (const bf16_t*)c->wrouter[l];
+            ma.w_gate_up = (const bf16_t*)c->wgu[l]; ma.w_down = (const bf16_t*)c->wdown[l];
+            ma.top_ids = c->at<int32_t>(L.moe_ids); ma.top_w = c->at<float>(L.moe_w);
+            ma.cnt = c->at<int32_t>(L.moe_cnt); ma.tile_off = c->at<int32_t>(L.moe_off);
+            ma.perm = c->at<int32_t>(L.moe_perm); ma.inv = c->at<int32_t>(L.moe_inv);
+            ma.act = c->at<bf16_t>(L.moe_act); ma.y = c->at<float>(L.moe_y); ma.out = part;
+            ma.T = T; ma.d = d; ma.E = m.n_experts; ma.top_k = m.top_k; ma.F = m.d_expert;
+            ProfScope prof(c, SV_PROF_MOE);
+            SV_HIP(c, moe_ffn(ma, st));
+            pending = 1;
+            continue;
+        }
         int s_gu = 1;
         SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
         SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, c->packed, st));
@@ -682,6 +714,54 @@ extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const fl
 extern "C" size_t sv_op_sample_scratch_bytes(int B, int N, int k) {
     if (B <= 0 || N <= 0 || k < 0) return 0;
     return align_up(sizeof(float) * 4 * (size_t)B * (1 + N * k)) + 3 * align_up(sizeof(int32_t) * (size_t)B * N);
+}
+
+struct MoeScratch { size_t ids, w, cnt, off, perm, inv, act, y, total; };
+static MoeScratch moe_scratch(int T, int d, int E, int top_k, int F) {
+    MoeScratch m;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+    const size_t tiles = (size_t)moe_max_tiles(T, E, top_k);
+    m.ids = take(sizeof(int32_t) * (size_t)T * top_k);
+    m.w = take(sizeof(float) * (size_t)T * top_k);
+    m.cnt = take(sizeof(int32_t) * E);
+    m.off = take(sizeof(int32_t) * (E + 1));
+    m.perm = take(sizeof(int32_t) * 32 * tiles);
+    m.inv = take(sizeof(int32_t) * (size_t)T * top_k);
+    m.act = take(sizeof(bf16_t) * 32 * tiles * F);
+    m.y = take(sizeof(float) * 32 * tiles * d);
+    m.total = o;
+    return m;
+}
+
+extern "C" size_t sv_op_moe_scratch_bytes(int T, int d, int E, int top_k, int F) {
+    if (!moe_shape_ok(T, d, E, top_k, F)) return 0;
+    return moe_scratch(T, d, E, top_k, F).total;
+}
+
+extern "C" int sv_op_moe_ffn(const void* a_packed, const void* w_router, const void* w_gate_up_packed,
+                             const void* w_down_packed, int T, int d, int E, int top_k, int F, void* scratch,
+                             size_t scratch_bytes, float* out, int32_t* top_ids, float* top_w, void* stream) {
+    if (!a_packed || !w_router || !w_gate_up_packed || !w_down_packed || !scratch || !out) return SV_EINVAL;
+    if (!moe_shape_ok(T, d, E, top_k, F)) return SV_EUNSUPPORTED;
+    const MoeScratch m = moe_scratch(T, d, E, top_k, F);
+    if (scratch_bytes < m.total || ((uintptr_t)scratch & 255)) return SV_EINVAL;
+    char* ws = reinterpret_cast<char*>(scratch);
+    MoeArgs ma;
+    ma.a = (const bf16_t*)a_packed; ma.w_router = (const bf16_t*)w_router;
+    ma.w_gate_up = (const bf16_t*)w_gate_up_packed; ma.w_down = (const bf16_t*)w_down_packed;
+    ma.top_ids = reinterpret_cast<int32_t*>(ws + m.ids); ma.top_w = reinterpret_cast<float*>(ws + m.w);
+    ma.cnt = reinterpret_cast<int32_t*>(ws + m.cnt); ma.tile_off = reinterpret_cast<int32_t*>(ws + m.off);
+    ma.perm = reinterpret_cast<int32_t*>(ws + m.perm); ma.inv = reinterpret_cast<int32_t*>(ws + m.inv);
+    ma.act = reinterpret_cast<bf16_t*>(ws + m.act); ma.y = reinterpret_cast<float*>(ws + m.y); ma.out = out;
+    ma.T = T; ma.d = d; ma.E = E; ma.top_k = top_k; ma.F = F;
+    hipStream_t st = (hipStream_t)stream;
+    if (moe_ffn(ma, st) != hipSuccess) return SV_EHIP;
+    if (top_ids && hipMemcpyAsync(top_ids, ma.top_ids, sizeof(int32_t) * (size_t)T * top_k, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return SV_EHIP;
+    if (top_w && hipMemcpyAsync(top_w, ma.top_w, sizeof(float) * (size_t)T * top_k, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return SV_EHIP;
+    return SV_OK;
 }
 
 extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, int k, int layer, const void* q, void* out) {

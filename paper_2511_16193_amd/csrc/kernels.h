@@ -72,6 +72,28 @@ struct AttnArgs {
 int attn_rows_pad(int n, int group);        // padded query rows per (request, kv head); 0 = MFMA path not applicable
 hipError_t attention(const AttnArgs& a, hipStream_t st);
 
+// ---- moe.hip ----
+struct MoeArgs {
+    const bf16_t* a;          // activations, packed [ceil(T/32)][d/16][64][8]
+    const bf16_t* w_router;   // [E][d] row-major
+    const bf16_t* w_gate_up;  // [E][2F][d] packed as one (E*2F) x d matrix
+    const bf16_t* w_down;     // [E][d][F] packed as one (E*d) x F matrix
+    int32_t* top_ids;         // [T][top_k] experts in descending probability
+    float* top_w;             // [T][top_k] renormalised weights
+    int32_t* cnt;             // [E] rows per expert
+    int32_t* tile_off;        // [E+1] first 32-row tile of each bucket
+    int32_t* perm;            // [32 * max_tiles] source row of a padded row
+    int32_t* inv;             // [T * top_k] padded row of an assignment
+    bf16_t* act;              // [max_tiles][F/16][64][8] SwiGLU outputs as operand tiles
+    float* y;                 // [32 * max_tiles][d] expert outputs
+    float* out;               // [T][d] combined result
+    int T, d, E, top_k, F;
+};
+int moe_shape_ok(int T, int d, int E, int top_k, int F);
+size_t moe_group_lds_bytes(int T, int E);
+int moe_max_tiles(int T, int E, int top_k);
+hipError_t moe_ffn(const MoeArgs& a, hipStream_t st);
+
 // ---- sampler.hip ----
 struct SampleArgs {
     const float* logits;                // [T][V]

@@ -1,0 +1,358 @@
+// Mixture-of-experts feed-forward of the verification pass on gfx950 (bf16 weights, fp32 accumulation):
+// softmax router -> top-k -> renormalised weights; rows bucketed by expert; per expert
+// (silu(x Wg^T) * (x Wu^T)) Wd^T; weighted combine.  The paper evaluates such a model (Section 5.3, the
+// Qwen3-235B MoE run); the FFN definition itself is the usual one of that model family.
+//
+// With a few dozen rows per expert the two expert products are bound by streaming the expert weights once
+// (1.2 GB a layer at 128 experts of 3 x 2048 x 768), so the kernels are built around that stream: one
+// work-group per (expert, strip of output features) pulls its strip of packed weight fragments straight
+// from HBM into registers through a ring of loads in flight, while the expert's rows (at most 128 at a time)
+// sit in LDS as MFMA operands.  Experts that received no row cost nothing.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace sv {
+
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+
+// ------------------------------------------------------------------ router
+// Four rows per work-group: the rows sit in LDS, each wave takes a quarter of the experts, the lanes of a wave
+// split the reduction of one expert's dot products and add their parts up in a fixed order.  Then one wave per
+// row: softmax over the experts, top_k by repeated arg-max (lowest id among equals), renormalisation.
+constexpr int kRouterRows = 4;
+
+__global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t* rows = reinterpret_cast<bf16_t*>(smem);                                 // [4][d]
+    float* logit = reinterpret_cast<float*>(smem + (size_t)kRouterRows * a.d * 2);  // [4][E]
+    const int t0 = blockIdx.x * kRouterRows;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pieces = a.d / 8;
+    for (int i = threadIdx.x; i < kRouterRows * pieces; i += 256) {
+        const int r = i / pieces, p = i % pieces;
+        const int t = t0 + r < a.T ? t0 + r : a.T - 1;
+        *reinterpret_cast<u32x4*>(rows + (size_t)r * a.d + 8 * p) =
+            *reinterpret_cast<const u32x4*>(a.a + act_index(t, 8 * p, a.d, true));
+    }
+    __syncthreads();
+    for (int e = wave; e < a.E; e += 4) {
+        float acc[kRouterRows] = {0.f, 0.f, 0.f, 0.f};
+        const bf16_t* w = a.w_router + (size_t)e * a.d;
+        for (int p = lane; p < pieces; p += 64) {
+            const u32x4 wv = *reinterpret_cast<const u32x4*>(w + 8 * p);
+#pragma unroll
+            for (int r = 0; r < kRouterRows; ++r) {
+                const u32x4 xv = *reinterpret_cast<const u32x4*>(rows + (size_t)r * a.d + 8 * p);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[r] = fmaf(__uint_as_float(wv[j] << 16), __uint_as_float(xv[j] << 16), acc[r]);
+                    acc[r] = fmaf(__uint_as_float(wv[j] & 0xffff0000u), __uint_as_float(xv[j] & 0xffff0000u), acc[r]);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kRouterRows; ++r) {
+            const float s = wave_sum(acc[r]);
+            if (lane == 0) logit[r * a.E + e] = s;
+        }
+    }
+    __syncthreads();
+    const int t = t0 + wave;
+    if (t >= a.T) return;
+    constexpr int PER = 4;                                   // experts per lane: E <= 256
+    float v[PER];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int e = lane + 64 * i;
+        v[i] = e < a.E ? logit[wave * a.E + e] : -INFINITY;
+        mx = fmaxf(mx, v[i]);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        v[i] = lane + 64 * i < a.E ? expf(v[i] - mx) : -1.f;  // -1 marks "not a candidate"
+        sum += v[i] > 0.f ? v[i] : 0.f;
+    }
+    sum = wave_sum(sum);
+    float kept_sum = 0.f, mine = 0.f;
+    int mine_id = 0;
+    for (int j = 0; j < a.top_k; ++j) {
+        float best = -1.f;
+        int best_e = 1 << 20;
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (v[i] > best) { best = v[i]; best_e = lane + 64 * i; }     // ascending ids: the first maximum is kept
+        const float top = wave_max(best);
+        const float cand = best == top ? -(float)best_e : -(float)(1 << 20);
+        int win = (int)(-wave_max(cand));                                   // lowest id among the equal maxima
+        if (win >= a.E) win = j;                                            // NaN inputs: still a valid expert id
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (lane + 64 * i == win) v[i] = -1.f;
+        const float p = top / sum;
+        kept_sum += p;
+        if (lane == j) { mine = p; mine_id = win; }
+    }
+    if (lane < a.top_k) {
+        a.top_ids[(size_t)t * a.top_k + lane] = mine_id;
+        a.top_w[(size_t)t * a.top_k + lane] = mine / kept_sum;
+    }
+}
+
+// ------------------------------------------------------------------ grouping
+// One work-group.  Every (row, expert) assignment sets bit `row` in its expert's bitmap (an OR: the result
+// does not depend on the order of the atomics); the rank of a row inside its expert's bucket is the number of
+// set bits below it.  Buckets are padded to whole 32-row tiles: bucket e owns padded rows
+// 32 * tile_off[e] .. 32 * tile_off[e+1] - 1; perm[padded row] = source row (padding rows name row 0, their
+// results are never read), inv[assignment] = padded row.
+__global__ __launch_bounds__(1024) void moe_group_kernel(MoeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int W = (a.T + 31) / 32;
+    uint32_t* bm = reinterpret_cast<uint32_t*>(smem);                               // [E][W]
+    uint16_t* below = reinterpret_cast<uint16_t*>(smem + (size_t)a.E * W * 4);      // [E][W] set bits in earlier words
+    int32_t* offs = reinterpret_cast<int32_t*>(smem + (size_t)a.E * W * 6);          // [E + 1] first tile of a bucket
+    int32_t* cnts = offs + a.E + 1;                                                  // [E]
+    const int n_asg = a.T * a.top_k;
+    for (int i = threadIdx.x; i < a.E * W; i += 1024) bm[i] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_asg; i += 1024) {
+        const int e = a.top_ids[i], t = i / a.top_k;
+        atomicOr(&bm[e * W + (t >> 5)], 1u << (t & 31));
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < a.E; e += 1024) {
+        int run = 0;
+        for (int w = 0; w < W; ++w) {
+            below[e * W + w] = (uint16_t)run;
+            run += __popc(bm[e * W + w]);
+        }
+        cnts[e] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tiles = 0;
+        for (int e = 0; e < a.E; ++e) {
+            offs[e] = tiles;
+            tiles += (cnts[e] + 31) / 32;
+        }
+        offs[a.E] = tiles;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e <= a.E; e += 1024) {
+        a.tile_off[e] = offs[e];
+        if (e < a.E) {
+            a.cnt[e] = cnts[e];
+            for (int r = cnts[e]; r < (offs[e + 1] - offs[e]) * 32; ++r) a.perm[offs[e] * 32 + r] = 0;
+        }
+    }
+    for (int i = threadIdx.x; i < n_asg; i += 1024) {
+        const int e = a.top_ids[i], t = i / a.top_k;
+        const int r = below[e * W + (t >> 5)] + __popc(bm[e * W + (t >> 5)] & ((1u << (t & 31)) - 1u));
+        const int prow = offs[e] * 32 + r;
+        a.inv[i] = prow;
+        a.perm[prow] = t;
+    }
+}
+
+// ------------------------------------------------------------------ expert products
+// MODE 0: rows gathered from the packed activations; waves 0,1 produce 64 gate features, waves 2,3 the 64 up
+//         features of the same indices; the epilogue forms silu(gate) * up and writes it, rounded to bf16, as
+//         packed MFMA operand tiles for MODE 1.
+// MODE 1: rows = those tiles; four waves produce 128 output features; fp32 results go to y[padded row][d].
+// A work-group handles the expert's row tiles four at a time (re-streaming its weight strip for experts with
+// more than 128 rows).  Products of row tiles beyond the bucket are skipped.
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void moe_gemm_kernel(MoeArgs a) {
+    constexpr int MT = 4, KA = 8, PD = 8;
+    __shared__ __attribute__((aligned(16))) unsigned char abuf[2][MT * KA * 1024];
+    const int K = MODE == 0 ? a.d : a.F;                    // reduction width
+    const int Ntot = MODE == 0 ? 2 * a.F : a.d;             // weight rows per expert
+    const int strips = MODE == 0 ? a.F / 64 : a.d / 128;
+    const int e = blockIdx.x / strips, p = blockIdx.x % strips;
+    const int tile0 = a.tile_off[e], ntile = a.tile_off[e + 1] - tile0;
+    if (ntile == 0) return;
+    const int kslices = K / 16, nfill = kslices / KA;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, lg = lane >> 5;
+
+    int nt_local;                                           // this wave's 32-feature tile among the expert's rows
+    if (MODE == 0) nt_local = wave < 2 ? 2 * p + wave : a.F / 32 + 2 * p + (wave - 2);
+    else nt_local = 4 * p + wave;
+    const int nt = e * (Ntot / 32) + nt_local;
+    const bf16_t* w_src = (MODE == 0 ? a.w_gate_up : a.w_down) + (((int64_t)(nt >> 2) * kslices) * 4 + (nt & 3)) * 512 + lane * 8;
+    constexpr int W_STEP = 4 * 512;
+
+    for (int g0 = 0; g0 < ntile; g0 += MT) {
+        const int nt_here = ntile - g0 < MT ? ntile - g0 : MT;
+        // wave w fills row tile w of the group (all KA slices of a fill); tiles past the bucket repeat its last
+        const int my_tile = tile0 + (g0 + wave < ntile ? g0 + wave : ntile - 1);
+        const bf16_t* a_src;
+        if (MODE == 0) {
+            const int t = a.perm[my_tile * 32 + l32];
+            a_src = a.a + ((int64_t)(t >> 5) * kslices) * 512 + ((t & 31) + 32 * lg) * 8;
+        } else {
+            a_src = a.act + ((int64_t)my_tile * kslices) * 512 + lane * 8;
+        }
+
+        floatx16 acc[MT];
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+
+        u32x4 wring[PD];
+#pragma unroll
+        for (int s = 0; s < PD; ++s)
+            wring[s] = *reinterpret_cast<const u32x4*>(w_src + (int64_t)(s < kslices ? s : kslices - 1) * W_STEP);
+        u32x4 areg[KA];
+#pragma unroll
+        for (int i = 0; i < KA; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src + (int64_t)i * 512);
+#pragma unroll
+        for (int i = 0; i < KA; ++i) *reinterpret_cast<u32x4*>(&abuf[0][(wave * KA + i) * 1024 + lane * 16]) = areg[i];
+
+        for (int fill = 0; fill < nfill; ++fill) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);             // own LDS writes done
+            __builtin_amdgcn_s_barrier();
+            const int nxt = fill + 1 < nfill ? fill + 1 : fill;
+#pragma unroll
+            for (int i = 0; i < KA; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src + (int64_t)(nxt * KA + i) * 512);
+            const unsigned char* ab = abuf[fill & 1] + lane * 16;
+            bf16x8 af[2][MT];
+#pragma unroll
+            for (int j = 0; j < MT; ++j) af[0][j] = *reinterpret_cast<const bf16x8*>(ab + (j * KA) * 1024);
+#pragma unroll
+            for (int s = 0; s < KA; ++s) {
+                const int slice = fill * KA + s;
+                if (s + 1 < KA) {
+#pragma unroll
+                    for (int j = 0; j < MT; ++j)
+                        af[(s + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(ab + (j * KA + s + 1) * 1024);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    if (j < nt_here)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wring[s % PD]),
+                                                                         af[s & 1][j], acc[j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                // refill the slot just consumed (after its readers, so the load lands in place)
+                const int ahead = slice + PD < kslices ? slice + PD : kslices - 1;
+                wring[s % PD] = *reinterpret_cast<const u32x4*>(w_src + (int64_t)ahead * W_STEP);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 0; i < KA; ++i)
+                *reinterpret_cast<u32x4*>(&abuf[(fill + 1) & 1][(wave * KA + i) * 1024 + lane * 16]) = areg[i];
+        }
+
+        if (MODE == 1) {
+#pragma unroll
+            for (int j = 0; j < MT; ++j) {
+                if (j < nt_here) {
+                    float* dst = a.y + ((int64_t)(tile0 + g0 + j) * 32 + l32) * a.d + p * 128 + wave * 32 + 4 * lg;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<floatx4*>(dst + 8 * q) =
+                            floatx4{acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();                   // every wave is done with abuf before the next group refills it
+        } else {
+            // up halves travel through LDS to the waves that hold the gate halves of the same features
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();                   // all reads of abuf are over
+            float* xbuf = reinterpret_cast<float*>(&abuf[0][0]);     // [2 waves][MT][16][64] floats = 32 KB
+            if (wave >= 2) {
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) xbuf[(((wave - 2) * MT + j) * 16 + q) * 64 + lane] = acc[j][q];
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            if (wave < 2) {
+                const int fs = (p * 64 + wave * 32) / 16;     // first 16-wide feature slice of this wave
+#pragma unroll
+                for (int j = 0; j < MT; ++j) {
+                    if (j < nt_here) {
+                        bf16_t* dst = a.act + ((int64_t)(tile0 + g0 + j) * (a.F / 16) + fs) * 512;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float r[4];
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float g = acc[j][4 * q + i];
+                                const float u = xbuf[((wave * MT + j) * 16 + 4 * q + i) * 64 + lane];
+                                r[i] = g / (1.0f + expf(-g)) * u;
+                            }
+                            // features 8q + 4 lg .. +3 of this wave's 32: slice q/2, half q%2, elements 4 lg ..
+                            u32x2 pk = {pack2bf(r[0], r[1]), pack2bf(r[2], r[3])};
+                            *reinterpret_cast<u32x2*>(dst + ((q >> 1) * 64 + l32 + 32 * (q & 1)) * 8 + 4 * lg) = pk;
+                        }
+                    }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();                   // xbuf is read before the next group overwrites it
+        }
+    }
+}
+
+// ------------------------------------------------------------------ combine
+// out[t][:] = sum over the row's top_k experts, in slot order, of weight * y[padded row of that assignment][:]
+__global__ __launch_bounds__(256) void moe_combine_kernel(MoeArgs a) {
+    const int t = blockIdx.x;
+    for (int c = threadIdx.x * 4; c < a.d; c += 1024) {
+        floatx4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < a.top_k; ++j) {
+            const float w = a.top_w[(size_t)t * a.top_k + j];
+            const floatx4 v = *reinterpret_cast<const floatx4*>(a.y + (int64_t)a.inv[(size_t)t * a.top_k + j] * a.d + c);
+            s[0] = fmaf(w, v[0], s[0]); s[1] = fmaf(w, v[1], s[1]); s[2] = fmaf(w, v[2], s[2]); s[3] = fmaf(w, v[3], s[3]);
+        }
+        *reinterpret_cast<floatx4*>(a.out + (int64_t)t * a.d + c) = s;
+    }
+}
+
+int moe_shape_ok(int T, int d, int E, int top_k, int F) {
+    if (T <= 0 || d <= 0 || E <= 0 || top_k <= 0 || F <= 0) return 0;
+    if (E % 64 != 0 || E > 256 || top_k > E || top_k > 64) return 0;       // router: four experts per lane, top_k <= lanes
+    if (d % 128 != 0 || F % 128 != 0) return 0;                            // eight 16-wide slices per fill; 128-feature strips
+    if (moe_group_lds_bytes(T, E) > 150 * 1024) return 0;
+    if ((size_t)kRouterRows * d * 2 + (size_t)kRouterRows * E * 4 > 150 * 1024) return 0;
+    return 1;
+}
+
+size_t moe_group_lds_bytes(int T, int E) {
+    const size_t W = (T + 31) / 32;
+    return (size_t)E * W * 6 + (size_t)(2 * E + 1) * 4 + 16;
+}
+
+int moe_max_tiles(int T, int E, int top_k) { return (T * top_k) / 32 + E; }
+
+hipError_t moe_ffn(const MoeArgs& a, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(moe_group_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(moe_router_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e1 != hipSuccess) return e1;
+        if (e2 != hipSuccess) return e2;
+        attr_set = true;
+    }
+    const size_t router_lds = (size_t)kRouterRows * a.d * 2 + (size_t)kRouterRows * a.E * 4;
+    hipLaunchKernelGGL(moe_router_kernel, dim3((a.T + kRouterRows - 1) / kRouterRows), dim3(256), router_lds, st, a);
+    hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(1024), moe_group_lds_bytes(a.T, a.E), st, a);
+    hipLaunchKernelGGL(moe_gemm_kernel<0>, dim3(a.E * (a.F / 64)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(moe_gemm_kernel<1>, dim3(a.E * (a.d / 128)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(moe_combine_kernel, dim3(a.T), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace sv
