@@ -34,9 +34,17 @@ def log(*a):
 
 
 def gemm_flops_per_step(s, T):
+    """Flops and launches of the dense projections (QKV, O, dense FFN, LM head) of one step."""
     qw, kvw = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
-    per_layer = s.d_model * (qw + 2 * kvw) + qw * s.d_model + 3 * s.d_model * s.d_ff
-    return 2.0 * T * (s.n_layers * per_layer + s.vocab * s.d_model), 4 * s.n_layers + 1
+    per_layer = s.d_model * (qw + 2 * kvw) + qw * s.d_model + (0 if s.n_experts else 3 * s.d_model * s.d_ff)
+    return 2.0 * T * (s.n_layers * per_layer + s.vocab * s.d_model), (2 if s.n_experts else 4) * s.n_layers + 1
+
+
+def moe_bytes_per_layer(s, T):
+    """HBM bytes one mixture-of-experts FFN has to move: every expert's three matrices once (with T * top_k
+    assignments far above the expert count every expert has rows), the router matrix, the rows in (bf16) and
+    the combined result out (fp32)."""
+    return s.n_experts * 3.0 * s.d_model * s.d_expert * 2 + s.n_experts * s.d_model * 2 + T * s.d_model * (2 + 4)
 
 
 def attention_bytes_per_layer(s, lengths, n):
@@ -146,9 +154,10 @@ def main():
     plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # the timed region: K steps, with the event brackets of the kernel kinds that carry the roofline
-    case.ver.profile_enable((1 << P.SV_PROF_GEMM) | (1 << P.SV_PROF_ATTENTION) | (1 << P.SV_PROF_SAMPLER))
+    case.ver.profile_enable((1 << P.SV_PROF_GEMM) | (1 << P.SV_PROF_ATTENTION) | (1 << P.SV_PROF_SAMPLER) |
+                            (1 << P.SV_PROF_MOE))
     run(1)
-    for kind in (P.SV_PROF_GEMM, P.SV_PROF_ATTENTION, P.SV_PROF_SAMPLER):
+    for kind in (P.SV_PROF_GEMM, P.SV_PROF_ATTENTION, P.SV_PROF_SAMPLER, P.SV_PROF_MOE):
         case.ver.profile_read(kind)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -158,10 +167,12 @@ def main():
     gemm_ms, gemm_n = case.ver.profile_read(P.SV_PROF_GEMM)
     attn_ms, attn_n = case.ver.profile_read(P.SV_PROF_ATTENTION)
     samp_ms, samp_n = case.ver.profile_read(P.SV_PROF_SAMPLER)
+    moe_ms, moe_n = case.ver.profile_read(P.SV_PROF_MOE)
     case.ver.profile_enable(0)
     log(f"step {ms_per_step:.3f} ms with event brackets ({plain_ms:.3f} ms without); per step: gemm "
         f"{gemm_ms / args.steps:.3f} ms / {gemm_n // args.steps} launches, attention {attn_ms / args.steps:.3f} ms / "
-        f"{attn_n // args.steps}, sampler {samp_ms / args.steps:.3f} ms")
+        f"{attn_n // args.steps}, sampler {samp_ms / args.steps:.3f} ms, moe {moe_ms / args.steps:.3f} ms / "
+        f"{moe_n // args.steps}")
 
     acc = out["accepted_len"].cpu().numpy()
     emitted = int((acc + 1).sum())
@@ -169,13 +180,21 @@ def main():
     abytes = attention_bytes_per_layer(shape, case.lengths, n)
     gemm_tflops = flops / gemm_launches / (gemm_ms / gemm_n * 1e-3) / 1e12
     attn_gbs = abytes / (attn_ms / attn_n * 1e-3) / 1e9
-    roof_gemm = {"kernel": "gemm_bf16_kernel (all projections + LM head)", "bound": "mfma", "achieved": gemm_tflops,
+    roof_gemm = {"kernel": "gemm_bf16_ws_kernel (all dense projections + LM head)", "bound": "mfma", "achieved": gemm_tflops,
                  "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
                  "avg_launch_ms": gemm_ms / gemm_n, "launches_per_step": gemm_n // args.steps}
     roof_attn = {"kernel": "attn_bf16_kernel + attn_merge_kernel (one layer)", "bound": "hbm", "achieved": attn_gbs,
                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": attn_gbs / PEAK_HBM_GBS, "traffic": None,
                  "avg_launch_ms": attn_ms / attn_n, "launches_per_step": attn_n // args.steps}
-    dominant, other = (roof_gemm, roof_attn) if gemm_ms >= attn_ms else (roof_attn, roof_gemm)
+    roofs = [(gemm_ms, roof_gemm), (attn_ms, roof_attn)]
+    if moe_n:
+        moe_gbs = moe_bytes_per_layer(shape, T) / (moe_ms / moe_n * 1e-3) / 1e9
+        roofs.append((moe_ms, {"kernel": "moe_gemm_kernel<0>, <1> + router, grouping, combine (one layer's expert FFN)",
+                               "bound": "hbm", "achieved": moe_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": moe_gbs / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": moe_ms / moe_n,
+                               "launches_per_step": moe_n // args.steps}))
+    roofs.sort(key=lambda x: -x[0])
+    dominant, other = roofs[0][1], [r for _, r in roofs[1:]]
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=case.device)
@@ -198,7 +217,7 @@ def main():
                    "verify": "stochastic, exponential-race draw, temperature 1.0"},
         "accepted_drafts_per_step": int(acc.sum()), "emitted_tokens_per_step": emitted,
         "accepted_drafts_tokens_per_s": int(acc.sum()) / (ms_per_step * 1e-3),
-        "roofline": dominant, "roofline_other": [other],
+        "roofline": dominant, "roofline_other": other,
         "sampler_ms_per_step": samp_ms / args.steps, "ms_per_step_without_event_brackets": plain_ms,
         "cpu_baseline": cpu,
     }

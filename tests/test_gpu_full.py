@@ -1,7 +1,8 @@
-"""Full-size parity: the benchmark workload (7B-shaped dense decoder, bf16, B=64, prefixes 1k-8k, k=4,
-stochastic verification) in the launch configuration bench.py times, checked against the oracle on a
-sample of requests (requests are independent through the whole step, so parity on a request is exact
-parity for that request) and against properties that hold for every request."""
+"""Full-size parity: the benchmark workloads (7B-shaped dense decoder, bf16, B=64, prefixes 1k-8k, k=4; and the
+mixture-of-experts decoder, 48 layers, 128 experts, B=128) with stochastic verification, in the launch
+configuration bench.py times, checked against the oracle on a sample of requests (requests are independent
+through the whole step, so parity on a request is exact parity for that request) and against properties that
+hold for every request."""
 import numpy as np
 import pytest
 import torch
@@ -15,8 +16,33 @@ pytestmark = pytest.mark.gpu
 
 
 def test_cfg2_full_size_sampled_requests_and_invariants():
+    run_full("cfg2", lambda lengths: sorted({int(np.argmin(lengths)), int(np.argmax(lengths)), 7}))
+
+
+ROUTE_CLEAR = 5e-3      # a router decision with a relative probability gap above this is the same on both sides
+                        # (measured: by layer 7 of the 48-layer run a gap between 2e-3 and 5e-3 has flipped)
+
+
+def test_cfg4_moe_full_size_sampled_request_and_invariants():
+    """All 48 layers at full width.  With random weights the router of a mixture-of-experts model is chaotic:
+    over 48 layers every row meets a decision (8th against 9th expert) closer than the ~1e-3 by which the
+    residual streams of the two sides differ, after which the row runs through other experts and its logits
+    are unrelated.  So the 48-layer run is compared, besides the properties that hold for every request, on
+    the cache entries of every layer reached before a row's first close decision; logits and decisions are
+    compared on the same model cut to two layers."""
+    # one request (the shortest prefix): the oracle widens ~40 experts' matrices to float64 per layer
+    run_full("cfg4", lambda lengths: [int(np.argmin(lengths))])
+
+
+def test_cfg4_moe_two_layers_full_width_logits_and_decisions():
+    run_full("cfg4", lambda lengths: sorted({int(np.argmin(lengths)), int(np.argmax(lengths)), 5, 40, 77, 120}), n_layers=2)
+
+
+def run_full(config, pick_sample, n_layers=None):
     from workloads.device_case import DeviceCase
-    shape = W.CONFIGS["cfg2"]
+    shape = W.CONFIGS[config]
+    if n_layers is not None:
+        shape = W.scaled_down(shape, n_layers=n_layers)
     print(f"[full] building {shape.name} on the device", flush=True)
     case = DeviceCase(shape)
     # drafts that do not come from the device path: q = softmax(N(0,1)) independent of the target
@@ -41,8 +67,8 @@ def test_cfg2_full_size_sampled_requests_and_invariants():
         assert case.ver.seq_len(b) == int(case.lengths[b]) + a + 1
     assert 0 < acc.sum() < B * k                      # both accepts and rejections occur
 
-    # ---- oracle on a sample: the shortest, the longest and one more request ----
-    sample = sorted({int(np.argmin(case.lengths)), int(np.argmax(case.lengths)), 7})
+    # ---- oracle on a sample (cfg2: the shortest, the longest and one more request) ----
+    sample = pick_sample(case.lengths)
     spec = M.ModelSpec(**shape.model_fields())
     wn = W.weights_to_numpy(case.weights, lazy=True)
     caches = []
@@ -64,7 +90,9 @@ def test_cfg2_full_size_sampled_requests_and_invariants():
     _, idx, vis = OV.new_token_layout(k, N)
     tokens = np.concatenate([x0[:, None], drafts[sample].reshape(len(sample), N * k)], axis=1)
     pos = np.array([c.length for c in caches])[:, None] + idx[None]
-    logits = M.forward(spec, wn, caches, tokens, pos, np.broadcast_to(vis, (len(sample), n, n)))
+    router_margins = []
+    logits = M.forward(spec, wn, caches, tokens, pos, np.broadcast_to(vis, (len(sample), n, n)),
+                       router_margins=router_margins)
     v = OV.verify_stochastic(logits, drafts[sample, 0], q[:, 0], u[:, 0], np.array(sample, dtype=np.uint64) * N,
                              1.0, OV.SAMPLE_EXP_RACE)
     dev_logits = out["logits"][sample].cpu().numpy().astype(np.float64)
@@ -80,8 +108,40 @@ def test_cfg2_full_size_sampled_requests_and_invariants():
     # layers as a random walk (measured: max 1.7e-2 after 1 layer, 2.4e-2 after 2, 5.4e-2 after 8,
     # 9.6e-2 after 28 on logits of standard deviation 1.2).  The 2e-2 bound holds per layer, not for 28:
     # here the bound is 2e-2 * sqrt(n_layers) on the maximum and 3 % of the logits' spread on the rms.
-    assert diff.max() < LOGIT_TOL["bf16"] * np.sqrt(shape.n_layers)
-    assert rel_rms < 3e-2
+    # Mixture-of-experts: a row whose router, in some layer, kept its last expert by a relative margin below
+    # the residual stream's ~1e-3 per-layer difference may keep another expert on the device; that row (and,
+    # through attention among the new tokens, later rows of its request) then differs by more.  Such rows
+    # are left out of the bound and reported.
+    ok_rows = np.ones((len(sample), n), dtype=bool)
+    if router_margins:
+        per_layer = np.stack(router_margins).reshape(shape.n_layers, len(sample), n)
+        # a row stays comparable while its own decisions and those of the rows it attends (the earlier new
+        # rows of its request) are clear in every layer so far
+        clear = np.cumsum(per_layer < ROUTE_CLEAR, axis=2) == 0                   # [layer, request, row]
+        clear_upto = np.cumsum(~clear, axis=0) == 0                                # all layers <= l clear
+        ok_rows = clear_upto[-1]
+        depth = clear_upto.sum(axis=0)                                             # layers passed cleanly
+        print(f"[full] layers passed before the first close router decision, per row: {depth.tolist()}; rows "
+              f"with all {shape.n_layers} clear: {int(ok_rows.sum())} of {ok_rows.size}", flush=True)
+        # cache entries of layer l depend on the decisions of layers < l
+        checked = 0
+        for i, b in enumerate(sample):
+            L = int(case.lengths[b])
+            for row in range(1 + int(acc[b])):
+                for l in range(min(shape.n_layers, int(depth[i, row]) + 1)):
+                    kd, vd = case.ver.kv_read(b, l, L + row, 1)
+                    ko, vo = caches[i].k[l][L + row], caches[i].v[l][L + row]
+                    kd, vd = kd.float().cpu().numpy()[0], vd.float().cpu().numpy()[0]
+                    tol = 0.02 + 0.005 * l          # one bf16 unit at the entries' magnitude, looser with depth
+                    assert np.max(np.abs(kd - ko)) < tol and np.max(np.abs(vd - vo)) < tol, (b, row, l)
+                    checked += 1
+        print(f"[full] cache entries compared at {checked} (row, layer) pairs", flush=True)
+        assert checked >= 2 * len(sample)
+    if ok_rows.any():
+        assert diff[ok_rows].max() < LOGIT_TOL["bf16"] * np.sqrt(shape.n_layers)
+        assert float(np.sqrt(np.mean(diff[ok_rows] ** 2)) / logits.std()) < 3e-2
+    elif n_layers is not None:
+        raise AssertionError("no comparable row in the shallow model")
     beyond = 0
     for i, b in enumerate(sample):
         a = int(v.accepted[i])
@@ -89,6 +149,8 @@ def test_cfg2_full_size_sampled_requests_and_invariants():
         got = list(toks[b, :acc[b] + 1])
         if a == acc[b] and want == got:
             continue
+        if not ok_rows[i].all():
+            continue                                          # a routing decision too close to call
         margin = min(float(v.accept_margin[i]), float(v.draw_margin[i]))
         allowed = max(1e-3, 2.0 * float(diff[i].max()))
         assert margin < allowed, (b, got, want, margin, float(diff[i].max()))

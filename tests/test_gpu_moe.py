@@ -25,6 +25,7 @@ def bf16_round(x: torch.Tensor) -> torch.Tensor:
     (777, 384, 128, 8, 256, 3.0),     # skewed router: a few experts take several hundred rows (more than one
                                       # group of four tiles), many take none; odd row count
     (5, 128, 64, 1, 128, 0.0),        # top-1, a single partial tile
+    (640, 2048, 128, 8, 768, 0.0),    # the benchmark's mixture-of-experts layer at full size (B=128, k=4)
 ])
 def test_moe_ffn_matches_oracle(T, d, E, top_k, F, skew):
     import paper_2511_16193_amd as P
@@ -67,11 +68,13 @@ def test_moe_ffn_matches_oracle(T, d, E, top_k, F, skew):
     if skew:
         counts = np.bincount(ids_o.reshape(-1), minlength=E)
         assert counts.max() > 128 and counts.min() == 0        # the case is what it says it is
-    # outputs: fp32 accumulation against float64, plus the rare bf16 rounding flip of one silu*up product,
-    # which moves an output by at most 2^-8 |act| |w_down| -- far below 1e-3 of the row's scale
+    # outputs: fp32 accumulation against float64 (~1e-6 of the row's scale), plus the rare bf16 rounding flip of
+    # one silu*up product: a flip moves the outputs of its row by 2^-8 |act| |w_down| each, up to ~2e-3 of the
+    # row's scale when |act| is a few units.  So: all but a small fraction within 1e-4, everything within 1e-2.
     scale = np.sqrt(np.mean(want[clear] ** 2, axis=1, keepdims=True))
     err = np.abs(out[clear] - want[clear])
-    assert np.all(err <= 1e-3 * scale + 1e-6), f"max error {err.max()} at scale {scale.mean()}"
+    assert np.mean(err > 1e-4 * scale + 1e-6) < 2e-2, f"fraction beyond 1e-4: {np.mean(err > 1e-4 * scale + 1e-6)}"
+    assert np.all(err <= 1e-2 * scale + 1e-6), f"max error {err.max()} at scale {scale.mean()}"
 
 
 MOE_SMALL = W.Shape("small-moe", 2, 256, 4, 2, 64, 0, 1024, n_experts=64, top_k=4, d_expert=128, dtype="bf16",
