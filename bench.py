@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--cpu-seqs", type=int, default=2, help="requests in the oracle sample (0 = skip)")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--attn-chunk", type=int, default=None, help="keys per split-KV chunk (tuning)")
     ap.add_argument("--drafts", choices=["noisy-target", "independent"], default="noisy-target",
                     help="independent: drafts from q = softmax(N(0,1)) without any device decoding step, so that "
                          "every kernel launch of the process has the timed step's shape (used for profiles)")
@@ -126,6 +127,8 @@ def main():
     case = DeviceCase(shape, k=args.k, log=log)
     if args.gemm_variant is not None:
         case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
+    if args.attn_chunk is not None:
+        case.ver.set_option(P.SV_OPT_ATTN_CHUNK_KEYS, args.attn_chunk)
     if args.drafts == "independent":
         log("drafting (target-independent q) ...")
         case.independent_drafts(1.0)

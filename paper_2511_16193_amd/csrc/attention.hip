@@ -32,7 +32,8 @@ template <int R>
 __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
     // work item = (request, chunk), listed by the host from its upper bounds of the lengths; the chunk
     // geometry comes from the true length: nch equal pieces, each a whole number of tiles
-    const int item = a.work[blockIdx.x], hkv = blockIdx.y;
+    // (the kv heads of an item are neighbours in launch order, so the list's longest-first order holds chip-wide)
+    const int item = a.work[blockIdx.x / a.Hkv], hkv = blockIdx.x % a.Hkv;
     const int b = item >> 16, chunk = item & 0xffff;
     const int seq = a.batch_seq[b];
     const int L = a.seq_len[seq];
@@ -353,7 +354,7 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
                        ? attn_rows_pad(a.n, G) : 0;
     if (rp) {
         const float sl2 = scale * 1.44269504088896340736f;
-        dim3 grid(a.n_work, a.Hkv);
+        dim3 grid(a.n_work * a.Hkv);
         switch (std::max(rp / 16, a.min_row_tiles)) {
             case 1: hipLaunchKernelGGL(attn_bf16_kernel<1>, grid, dim3(256), 0, st, a, sl2); break;
             case 2: hipLaunchKernelGGL(attn_bf16_kernel<2>, grid, dim3(256), 0, st, a, sl2); break;

@@ -181,7 +181,8 @@ struct sv_ctx {
     bool packed;                                          // projection weights are in fragment order
     bool attn_generic;
     int attn_min_rt;
-    int attn_chunk;                                       // keys per split-KV chunk (multiple of kChunkKeys)
+    int attn_chunk;                                       // keys per split-KV chunk of the staged batch
+    int attn_chunk_opt;                                   // 0 = chosen per batch, else fixed by option
     unsigned prof_mask;                                   // kinds of kernels to time with events
     struct ProfRec { int kind; hipEvent_t a, b; };
     std::vector<ProfRec> prof_recs;                       // recorded, not yet read
@@ -310,6 +311,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->attn_generic = false;
     c->attn_min_rt = 1;
     c->attn_chunk = kChunkKeys;
+    c->attn_chunk_opt = 0;
     c->prof_mask = 0;
     const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8 + L.max_chunks) + 8;
     for (int i = 0; i < kRing; ++i) { c->staging[i] = nullptr; c->staged[i] = nullptr; c->staged_valid[i] = false; }
@@ -468,19 +470,37 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
         SV_HIP(c, hipGetLastError());
     }
     // attention work list: every (request, chunk) that can exist given the upper bounds of the lengths,
-    // whole chunks first, the requests' last (shorter) pieces after them, longest first
+    // longest pieces first (the hardware hands work-groups to CUs in order, so this is longest-processing-
+    // time-first list scheduling).  Keys per chunk, unless fixed by option: the candidate that minimises
+    // (all keys + a fixed cost per work-group, measured at ~350 keys' worth) / 256 CUs + half a work-group
+    // for the ragged end.
     {
+        int chunk = c->attn_chunk_opt;
+        if (chunk == 0) {
+            double best = 1e300;
+            for (int cand : {1024, 1536, 2048, 3072, 4096, 6144, 8192}) {
+                double keys = 0, groups = 0;
+                for (int b = 0; b < B; ++b) {
+                    const int total = c->seqs[ids[b]].len_ub + extra;
+                    keys += total;
+                    groups += (total + cand - 1) / cand;
+                }
+                const double ov = 350.0, heads = c->model.n_kv_heads;
+                const double cost = (keys + groups * ov) * heads / 256.0 + 0.5 * (cand + ov);
+                if (cost < best) { best = cost; chunk = cand; }
+            }
+        }
+        c->attn_chunk = chunk;
         int32_t* work = upd + 3 * nupd;
-        int nw = 0;
-        std::vector<std::pair<int, int>> tails;
+        std::vector<std::pair<int, int>> items;
         for (int b = 0; b < B; ++b) {
             const int total = c->seqs[ids[b]].len_ub + extra;
-            const int nch = std::min((total + c->attn_chunk - 1) / c->attn_chunk, c->lay.max_chunks);
-            for (int ch = 0; ch + 1 < nch; ++ch) work[nw++] = (b << 16) | ch;
-            if (nch > 0) tails.push_back({-(total - (nch - 1) * (total / nch)), (b << 16) | (nch - 1)});
+            const int nch = std::min((total + chunk - 1) / chunk, c->lay.max_chunks);
+            for (int ch = 0; ch < nch; ++ch) items.push_back({-(total / nch), (b << 16) | ch});
         }
-        std::sort(tails.begin(), tails.end());
-        for (auto& t : tails) work[nw++] = t.second;
+        std::stable_sort(items.begin(), items.end(), [](const std::pair<int, int>& x, const std::pair<int, int>& y) { return x.first < y.first; });
+        int nw = 0;
+        for (auto& t : items) work[nw++] = t.second;
         SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.work), work, nw * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
         c->n_work = nw;
     }
@@ -847,8 +867,8 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
             c->attn_generic = value != 0;
             return SV_OK;
         case SV_OPT_ATTN_CHUNK_KEYS:
-            if (value < kChunkKeys || value % kChunkKeys != 0) return c->fail(SV_EINVAL, "chunk of %d keys", value);
-            c->attn_chunk = value;
+            if (value != 0 && (value < kChunkKeys || value % kChunkKeys != 0)) return c->fail(SV_EINVAL, "chunk of %d keys", value);
+            c->attn_chunk_opt = value;
             return SV_OK;
         case SV_OPT_ATTN_MIN_ROW_TILES:
             if (value < 1 || value > 4) return c->fail(SV_EINVAL, "row tiles %d", value);
