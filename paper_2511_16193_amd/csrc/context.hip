@@ -603,9 +603,15 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
             pending = 1;
             continue;
         }
-        int s_gu = 1;
-        SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
-        SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, c->packed, st));
+        if (c->packed && m.d_ff % 64 == 0) {
+            // gate/up projection with SwiGLU in its epilogue: the [T, 2F] fp32 intermediate never exists
+            ProfScope prof(c, SV_PROF_GEMM);
+            SV_HIP(c, gemm_bf16_ws_glu((const bf16_t*)a_norm, (const bf16_t*)c->wgu[l], c->at<bf16_t>(L.act), T, m.d_ff, d, st));
+        } else {
+            int s_gu = 1;
+            SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
+            SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, c->packed, st));
+        }
         SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
     }
     SV_HIP(c, add_rmsnorm(h, part, pending, c->final_norm, a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));

@@ -291,10 +291,11 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(
 // reads, PD k-slices ahead, with no LDS and no barrier on that path.  Only the activations, which every
 // wave needs, go through LDS: KA 16-wide slices of all MT 32-token tiles per fill (packed order too, so
 // a fill is a handful of contiguous 1 KB copies), double buffered, one barrier per fill.
-template <int MT, int NT, int KA, int PD>
+template <int MT, int NT, int KA, int PD, bool GLU = false>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
     const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
     int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n) {
+    static_assert(!GLU || NT == 1, "the gated form pairs two half strips");
     constexpr int BM = 32 * MT, BN = 128 * NT;
     constexpr int AFR = MT * KA;                          // activation fragments per fill
     static_assert(AFR % 4 == 0, "fill must split over 4 waves");
@@ -330,7 +331,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
     const bf16_t* w_src[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-        const int nt = n0 / 32 + wave * NT + i;
+        // gated form (N = 2F weight rows, gate rows first): work-group tn covers features 64 tn .. 64 tn + 63;
+        // waves 0,1 stream their gate rows, waves 2,3 the up rows of the same features
+        const int nt = GLU ? (wave < 2 ? 2 * tn + wave : N / 64 + 2 * tn + (wave - 2)) : n0 / 32 + wave * NT + i;
         w_src[i] = Wp + (((int64_t)(nt >> 2) * kslices + ks0) * 4 + (nt & 3)) * 512 + lane * 8;
     }
     constexpr int W_STEP = 4 * 512;                       // elements between consecutive slices of a tile
@@ -406,6 +409,47 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
             *reinterpret_cast<u32x4*>(&abuf[(fill + 1) & 1][(wave * APW + i) * 1024 + lane * 16]) = areg[i];
     }
 
+    if (GLU) {
+        // up halves travel through LDS to the waves that hold the gate halves; those write
+        // silu(gate) * up, rounded to bf16, as packed operand tiles [M/32][F/16][64][8] of the next projection
+        const int F = N / 2;
+        bf16_t* act = reinterpret_cast<bf16_t*>(out);
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();                        // every wave is done reading the activations
+        float* xbuf = reinterpret_cast<float*>(&abuf[0][0]); // [2 waves][MT][16][64] floats
+        static_assert(2 * MT * 16 * 64 * 4 <= 2 * AFR * 1024, "exchange area");
+        if (wave >= 2) {
+#pragma unroll
+            for (int j = 0; j < MT; ++j)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) xbuf[(((wave - 2) * MT + j) * 16 + q) * 64 + lane] = acc[0][j][q];
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        if (wave < 2) {
+            const int fs = (tn * 64 + wave * 32) / 16;
+#pragma unroll
+            for (int j = 0; j < MT; ++j) {
+                const int mt = m0 / 32 + j;
+                if (mt < m_tiles_total) {
+                    bf16_t* dst = act + ((int64_t)mt * (F / 16) + fs) * 512;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float r[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float g = acc[0][j][4 * q + i];
+                            const float u = xbuf[((wave * MT + j) * 16 + 4 * q + i) * 64 + lane];
+                            r[i] = g / (1.0f + expf(-g)) * u;
+                        }
+                        u32x2 pk = {pack2bf(r[0], r[1]), pack2bf(r[2], r[3])};
+                        *reinterpret_cast<u32x2*>(dst + ((q >> 1) * 64 + l32 + 32 * (q & 1)) * 8 + 4 * lg) = pk;
+                    }
+                }
+            }
+        }
+        return;
+    }
     float* dst = out + (int64_t)sp * M * N;
 #pragma unroll
     for (int j = 0; j < MT; ++j) {
@@ -451,6 +495,20 @@ static hipError_t launch_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int 
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     hipLaunchKernelGGL((gemm_bf16_ws_kernel<MT, NT, KA, PD>), dim3(tiles_m * tiles_n * splits), dim3(256), 0, st, Ap, Wp,
                        out, M, N, K, K / splits, splits, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// Gate/up projection fused with SwiGLU: Wp packed [2F, K] (gate rows, then up rows); act_out packed
+// [ceil(M/32)*32, F] bf16.  F a multiple of 64.
+hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st) {
+    if (F % 64 != 0 || K % 64 != 0) return hipErrorInvalidValue;
+    const int tiles_m = (M + 159) / 160, tiles_n = F / 64;
+    if (K % 128 == 0)
+        hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 1, 8, 8, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, Ap, Wp,
+                           reinterpret_cast<float*>(act_out), M, 2 * F, K, K, 1, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 1, 4, 4, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, Ap, Wp,
+                           reinterpret_cast<float*>(act_out), M, 2 * F, K, K, 1, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
