@@ -292,7 +292,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(
 // wave needs, go through LDS: KA 16-wide slices of all MT 32-token tiles per fill (packed order too, so
 // a fill is a handful of contiguous 1 KB copies), double buffered, one barrier per fill.
 template <int MT, int NT, int KA, int PD, bool GLU = false>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_ws_kernel(
+__global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void gemm_bf16_ws_kernel(
     const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
     int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n) {
     static_assert(!GLU || NT == 1, "the gated form pairs two half strips");
