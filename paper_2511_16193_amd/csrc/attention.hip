@@ -32,8 +32,15 @@ template <int R>
 __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
     // work item = (request, chunk), listed by the host from its upper bounds of the lengths; the chunk
     // geometry comes from the true length: nch equal pieces, each a whole number of tiles
-    // (the kv heads of an item are neighbours in launch order, so the list's longest-first order holds chip-wide)
-    const int item = a.work[blockIdx.x / a.Hkv], hkv = blockIdx.x % a.Hkv;
+    // Launch order: the kv heads of an item are neighbours, so the list's longest-first order holds chip-wide.
+    // With more than 64 stacked rows the row tiles are split over row_groups work-groups that stream the same
+    // keys; work-group ids 8 apart run on the same XCD, so the groups of one (item, head) are placed 8 apart
+    // and started together: the second reader of a tile finds it in that XCD's L2.
+    const int slot = blockIdx.x / (8 * a.row_groups), rem = blockIdx.x % (8 * a.row_groups);
+    const int rg = rem >> 3, pair = slot * 8 + (rem & 7);
+    if (pair >= a.n_work * a.Hkv) return;
+    const int item = a.work[pair / a.Hkv], hkv = pair % a.Hkv;
+    const int row0 = rg * R * 16;                         // first stacked row of this work-group
     const int b = item >> 16, chunk = item & 0xffff;
     const int seq = a.batch_seq[b];
     const int L = a.seq_len[seq];
@@ -59,7 +66,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     u32x4 qf[R][4];
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
-        const int r = rt * 16 + l16;
+        const int r = row0 + rt * 16 + l16;
         const bool ok = r < rows;
         const int j = ok ? r / G : 0, hl = ok ? r % G : 0;
         const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (((int64_t)b * a.n + j) * a.Hq + hkv * G + hl) * HD;
@@ -73,7 +80,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     int vis_lo[R], vis_hi[R];
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
-        const int r = rt * 16 + l16;
+        const int r = row0 + rt * 16 + l16;
         const int j = r < rows ? r / G : 0;
         vis_lo[rt] = j > 0 ? L + 1 + row_chain(j, a.k) * a.k : 0;
         vis_hi[rt] = j > 0 ? vis_lo[rt] + row_index_in_chain(j, a.k) : 0;
@@ -260,8 +267,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
         }
         __syncthreads();
     }
-    const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.max_chunks + chunk) * RP;
-    for (int e = tid; e < rows * HD; e += 256) {
+    const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.max_chunks + chunk) * a.rows_pad + row0;
+    const int rows_here = min(rows - row0, RP);
+    for (int e = tid; e < rows_here * HD; e += 256) {
         const int r = e / HD, d = e % HD;
         a.part_o[(pbase + r) * HD + d] = o_sh[d][r];
     }
@@ -269,14 +277,17 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
 #pragma unroll
         for (int rt = 0; rt < R; ++rt) {
             const int r = rt * 16 + l16;
-            a.part_ml[(pbase + r) * 2] = m_all[rt];
-            a.part_ml[(pbase + r) * 2 + 1] = l_all[rt];
+            if (r < rows_here) {
+                a.part_ml[(pbase + r) * 2] = m_all[rt];
+                a.part_ml[(pbase + r) * 2 + 1] = l_all[rt];
+            }
         }
     }
 }
 
 // Combine the chunk partials of one (row, q head): out = sum_c 2^(m_c - M) O_c / sum_c 2^(m_c - M) l_c.
-__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, int rows_pad) {
+__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a) {
+    const int rows_pad = a.rows_pad;
     const int t = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
     const int b = t / a.n, j = t % a.n;
     const int G = a.Hq / a.Hkv, hkv = h / G, r = j * G + h % G;
@@ -342,7 +353,7 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnArgs a, float scal
 
 int attn_rows_pad(int n, int group) {
     const int rows = n * group;
-    if (rows > 64) return 0;
+    if (rows > 256) return 0;
     return (rows + 15) / 16 * 16;
 }
 
@@ -352,18 +363,23 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
     const int rp = (!a.force_generic && a.dtype == 1 && a.hd == HD && a.geom.page_size % TILE_KEYS == 0 &&
                     (a.geom.page_size & (a.geom.page_size - 1)) == 0 && a.chunk_keys % 128 == 0)
                        ? attn_rows_pad(a.n, G) : 0;
-    if (rp) {
+    if (rp && rp <= a.rows_pad) {
         const float sl2 = scale * 1.44269504088896340736f;
-        dim3 grid(a.n_work * a.Hkv);
-        switch (std::max(rp / 16, a.min_row_tiles)) {
-            case 1: hipLaunchKernelGGL(attn_bf16_kernel<1>, grid, dim3(256), 0, st, a, sl2); break;
-            case 2: hipLaunchKernelGGL(attn_bf16_kernel<2>, grid, dim3(256), 0, st, a, sl2); break;
-            case 3: hipLaunchKernelGGL(attn_bf16_kernel<3>, grid, dim3(256), 0, st, a, sl2); break;
-            default: hipLaunchKernelGGL(attn_bf16_kernel<4>, grid, dim3(256), 0, st, a, sl2); break;
+        // up to four 16-row tiles per work-group; more stacked rows are split over row groups
+        AttnArgs b = a;
+        const int tiles = rp / 16;
+        b.row_groups = (tiles + 3) / 4;
+        const int R = b.row_groups == 1 ? std::max(tiles, a.min_row_tiles) : (tiles + b.row_groups - 1) / b.row_groups;
+        dim3 grid((a.n_work * a.Hkv + 7) / 8 * 8 * b.row_groups);
+        switch (R) {
+            case 1: hipLaunchKernelGGL(attn_bf16_kernel<1>, grid, dim3(256), 0, st, b, sl2); break;
+            case 2: hipLaunchKernelGGL(attn_bf16_kernel<2>, grid, dim3(256), 0, st, b, sl2); break;
+            case 3: hipLaunchKernelGGL(attn_bf16_kernel<3>, grid, dim3(256), 0, st, b, sl2); break;
+            default: hipLaunchKernelGGL(attn_bf16_kernel<4>, grid, dim3(256), 0, st, b, sl2); break;
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, a.Hq), dim3(HD), 0, st, a, std::max(rp, 16 * a.min_row_tiles));
+        hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, a.Hq), dim3(HD), 0, st, b);
         return hipGetLastError();
     }
     dim3 grid(a.B * a.n, a.Hq);

@@ -123,8 +123,8 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.act = take(es * Tp * F);
     L.logits = take(sizeof(float) * (size_t)T * m.vocab);
     const int G = m.n_q_heads / std::max(1, m.n_kv_heads);
-    L.rows_pad = 64;
-    (void)G;
+    // the MFMA attention stacks G * n rows per kv head; its chunk partials are kept for up to 256 of them
+    L.rows_pad = std::max(64, std::min(256, (G * (1 + r.max_chains * r.max_k) + 15) / 16 * 16));
     L.part_o = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * m.head_dim);
     L.part_ml = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * 2);
     L.moe_ids = L.moe_w = L.moe_cnt = L.moe_off = L.moe_perm = L.moe_inv = L.moe_act = L.moe_y = 0;
@@ -575,7 +575,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.q = ra.q_out; aa.pool = c->rt.kv_pool; aa.geom = c->geom; aa.layer = l;
         aa.page_table = ra.page_table; aa.max_pages_per_seq = c->rt.max_pages_per_seq;
         aa.batch_seq = rp.batch_seq; aa.seq_len = rp.seq_len; aa.out = c->at<void>(L.attn);
-        aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml);
+        aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml); aa.rows_pad = L.rows_pad; aa.row_groups = 1;
         aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
         aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work;
         aa.out_packed = c->packed;
@@ -803,7 +803,7 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.q = q; aa.pool = c->rt.kv_pool; aa.geom = c->geom; aa.layer = layer;
     aa.page_table = c->at<int32_t>(c->lay.page_table); aa.max_pages_per_seq = c->rt.max_pages_per_seq;
     aa.batch_seq = c->at<int32_t>(c->lay.batch_seq); aa.seq_len = c->at<int32_t>(c->lay.seq_len); aa.out = out;
-    aa.part_o = c->at<float>(c->lay.part_o); aa.part_ml = c->at<float>(c->lay.part_ml);
+    aa.part_o = c->at<float>(c->lay.part_o); aa.part_ml = c->at<float>(c->lay.part_ml); aa.rows_pad = c->lay.rows_pad; aa.row_groups = 1;
     aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
     aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(c->lay.work); aa.n_work = c->n_work;
     aa.out_packed = false;

@@ -62,6 +62,8 @@ struct AttnArgs {
     const int32_t* seq_len;             // [max_seqs]
     void* out;                          // [T][Hq*hd] storage type
     float* part_o;                      // [B][Hkv][max_chunks][rows_pad][hd]
+    int rows_pad;                       // row pitch of the partials (a multiple of 16, >= stacked rows for the MFMA path)
+    int row_groups;                     // set by attention(): work-groups that share one (item, head)
     float* part_ml;                     // [B][Hkv][max_chunks][rows_pad][2]
     int B, n, k, Hq, Hkv, hd, dtype;
     int chunk_keys, max_chunks;

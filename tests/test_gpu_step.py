@@ -73,6 +73,9 @@ SMALL_BF16 = W.Shape("small-bf16", 3, 256, 8, 2, 128, 512, 2048, dtype="bf16", b
     (3, 3, OV.GREEDY, 0, True),
     (3, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, False),
     (3, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),
+    (6, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),     # 76 stacked rows per kv head: two row groups of 3 tiles
+    (8, 3, OV.GREEDY, 0, True),                          # 100 stacked rows: two row groups of 4 tiles (the 32B
+                                                         # configuration's three chains of eight drafts)
 ])
 def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed):
     """bf16 decoder small enough for the oracle (3 layers, d 256, 8 q / 2 kv heads x 128, vocab 2048) over a
