@@ -98,6 +98,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None, help="requests per step (default: the configuration's)")
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--cpu-seqs", type=int, default=2, help="requests in the oracle sample (0 = skip)")
     ap.add_argument("--gemm-variant", type=int, default=None)
@@ -124,6 +125,8 @@ def main():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(1)
     shape = W.CONFIGS[args.config]
+    if args.batch is not None:
+        shape = W.scaled_down(shape, batch=args.batch)
     case = DeviceCase(shape, k=args.k, log=log)
     if args.gemm_variant is not None:
         case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
@@ -215,7 +218,7 @@ def main():
         "metric": "accepted tokens/s of batched spec-verify step", "value": emitted / (ms_per_step * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": shape.name, "batch": B, "k": k, "chains": N, "rows_per_step": T,
+        "config": {"workload": shape.name + (f" at batch {B}" if args.batch is not None else ""), "batch": B, "k": k, "chains": N, "rows_per_step": T,
                    "prefix_tokens": int(case.lengths.sum()), "drafts": args.drafts, "draft_sigma": list(shape.draft_sigma) if args.sigma is None else [args.sigma],
                    "verify": "stochastic, exponential-race draw, temperature 1.0"},
         "accepted_drafts_per_step": int(acc.sum()), "emitted_tokens_per_step": emitted,

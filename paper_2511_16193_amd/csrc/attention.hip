@@ -285,10 +285,12 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     }
 }
 
-// Combine the chunk partials of one (row, q head): out = sum_c 2^(m_c - M) O_c / sum_c 2^(m_c - M) l_c.
-__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a) {
+// Combine the chunk partials of one row: out = sum_c 2^(m_c - M) O_c / sum_c 2^(m_c - M) l_c.  A thread
+// owns four consecutive dimensions of one q head; a work-group covers 256 / 32 = 8 heads of the row.
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     const int rows_pad = a.rows_pad;
-    const int t = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+    const int t = blockIdx.x, h = blockIdx.y * 8 + (threadIdx.x >> 5), d = (threadIdx.x & 31) * 4;
+    if (h >= a.Hq) return;
     const int b = t / a.n, j = t % a.n;
     const int G = a.Hq / a.Hkv, hkv = h / G, r = j * G + h % G;
     const int total = a.seq_len[a.batch_seq[b]] + a.n;
@@ -298,14 +300,19 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a) {
     const int64_t base = ((int64_t)b * a.Hkv + hkv) * a.max_chunks;
     float M = -INFINITY;
     for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((base + c) * rows_pad + r) * 2]);
-    float num = 0.f, den = 0.f;
+    floatx4 num = {0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
     for (int c = 0; c < nch; ++c) {
         const int64_t pr = (base + c) * rows_pad + r;
-        const float f = exp2f(a.part_ml[pr * 2] - M);
-        den += f * a.part_ml[pr * 2 + 1];
-        num += f * a.part_o[pr * HD + d];
+        const floatx2 ml = *reinterpret_cast<const floatx2*>(a.part_ml + pr * 2);
+        const float f = exp2f(ml.x - M);
+        den += f * ml.y;
+        const floatx4 o = *reinterpret_cast<const floatx4*>(a.part_o + pr * HD + d);
+        num[0] += f * o[0]; num[1] += f * o[1]; num[2] += f * o[2]; num[3] += f * o[3];
     }
-    reinterpret_cast<bf16_t*>(a.out)[act_index(t, h * HD + d, a.Hq * HD, a.out_packed)] = f2bf(num / den);
+    // four consecutive dimensions stay inside one 8-element piece of either output order
+    u32x2 pk = {pack2bf(num[0] / den, num[1] / den), pack2bf(num[2] / den, num[3] / den)};
+    *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(a.out) + act_index(t, h * HD + d, a.Hq * HD, a.out_packed)) = pk;
 }
 
 // Generic path: one wave per (new row, q head).  Lane-strided keys, per-lane online softmax with the
@@ -379,7 +386,7 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, a.Hq), dim3(HD), 0, st, b);
+        hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, (a.Hq + 7) / 8), dim3(256), 0, st, b);
         return hipGetLastError();
     }
     dim3 grid(a.B * a.n, a.Hq);

@@ -29,10 +29,16 @@ template <typename T> struct Store;
 template <> struct Store<float> {
     static __device__ __forceinline__ float load(const float* p) { return *p; }
     static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void store4(float* p, const float* v) {      // p 16-byte aligned
+        *reinterpret_cast<floatx4*>(p) = floatx4{v[0], v[1], v[2], v[3]};
+    }
 };
 template <> struct Store<bf16_t> {
     static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(*p); }
     static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f2bf(v); }
+    static __device__ __forceinline__ void store4(bf16_t* p, const float* v) {     // p 8-byte aligned
+        *reinterpret_cast<u32x2*>(p) = u32x2{pack2bf(v[0], v[1]), pack2bf(v[2], v[3])};
+    }
 };
 
 // ---- paged KV layout -------------------------------------------------------

@@ -52,16 +52,22 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
         const int i = threadIdx.x + v * 256;
         x[v] = i < nq ? hr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    for (int s = 0; s < S; ++s) {
-        const floatx4* pr = reinterpret_cast<const floatx4*>(part + s * part_stride + (int64_t)t * d);
-        floatx4 y[NV];
+    // partial planes four at a time: all their loads are in flight together, the additions keep plane order
+    for (int s0 = 0; s0 < S; s0 += 4) {
+        floatx4 y[4][NV];
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int i = threadIdx.x + v * 256;
-            y[v] = i < nq ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < 4; ++u) {
+            const floatx4* pr = reinterpret_cast<const floatx4*>(part + (s0 + u < S ? s0 + u : s0) * part_stride + (int64_t)t * d);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int i = threadIdx.x + v * 256;
+                y[u][v] = (i < nq) & (s0 + u < S) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+            }
         }
 #pragma unroll
-        for (int v = 0; v < NV; ++v) x[v] = x[v] + y[v];
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) x[v] = x[v] + y[u][v];
     }
     float ss = 0.f;
 #pragma unroll
@@ -84,9 +90,11 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
     for (int v = 0; v < NV; ++v) {
         const int i = threadIdx.x + v * 256;
         if (i < nq) {
+            float o[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                Store<T>::store(a + act_index(t, 4 * i + e, d, packed), x[v][e] * r * Store<T>::load(w + 4 * i + e));
+            for (int e = 0; e < 4; ++e) o[e] = x[v][e] * r * Store<T>::load(w + 4 * i + e);
+            // four consecutive columns are contiguous in either output order
+            Store<T>::store4(a + act_index(t, 4 * i, d, packed), o);
         }
     }
 }
