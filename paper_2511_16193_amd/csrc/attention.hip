@@ -28,10 +28,9 @@ constexpr int TILE_KEYS = 32;
 
 struct KTile { u32x4 k[2][4]; u32x4 v[8]; };
 
-template <int R>
-__global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
-    // work item = (request, chunk), listed by the host from its upper bounds of the lengths; the chunk
-    // geometry comes from the true length: nch equal pieces, each a whole number of tiles
+template <int R, int DEPTH>
+__global__ __launch_bounds__(256, R == 1 ? 2 : 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
+    // work item = one piece of one request's keys, cut by the host from its upper bounds of the lengths.
     // Launch order: the kv heads of an item are neighbours, so the list's longest-first order holds chip-wide.
     // With more than 64 stacked rows the row tiles are split over row_groups work-groups that stream the same
     // keys; work-group ids 8 apart run on the same XCD, so the groups of one (item, head) are placed 8 apart
@@ -39,18 +38,16 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     const int slot = blockIdx.x / (8 * a.row_groups), rem = blockIdx.x % (8 * a.row_groups);
     const int rg = rem >> 3, pair = slot * 8 + (rem & 7);
     if (pair >= a.n_work * a.Hkv) return;
-    const int item = a.work[pair / a.Hkv], hkv = pair % a.Hkv;
-    const int row0 = rg * R * 16;                         // first stacked row of this work-group
-    const int b = item >> 16, chunk = item & 0xffff;
-    const int seq = a.batch_seq[b];
+    const int hkv = pair % a.Hkv;
+    const int4 item = reinterpret_cast<const int4*>(a.work)[pair / a.Hkv];
+    const int b = item.x >> 16, chunk = item.x & 0xffff;
+    const int seq = item.y;
     const int L = a.seq_len[seq];
     const int total = L + a.n;
-    const int nch = (total + a.chunk_keys - 1) / a.chunk_keys;
-    if (chunk >= nch) return;
-    const int clen = ((total + nch - 1) / nch + TILE_KEYS - 1) / TILE_KEYS * TILE_KEYS;
-    const int kbeg = chunk * clen;
-    if (kbeg >= total) return;
-    const int kend = min(kbeg + clen, total);
+    const int kbeg = item.z;
+    if (kbeg >= total) return;                            // the live length fell short of the host's bound
+    const int kend = min(item.w, total);
+    const int row0 = rg * R * 16;                         // first stacked row of this work-group
     const int G = a.Hq / a.Hkv, rows = G * a.n;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -97,18 +94,31 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
         for (int ht = 0; ht < 8; ++ht) o[ht][rt] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // The tile's base address is wave-uniform (scalar page number, head, offset): it is kept in scalar registers
+    // and every load is "scalar base + lane offset + immediate".  With per-lane 64-bit addresses in vector
+    // registers the compiler, short of registers, computed the next tile's address into registers that an
+    // in-flight load was still to fill, and had to wait for that load -- and, loads returning in order, for the
+    // whole previous tile -- before it could issue the rest: the prefetch never overlapped anything.
+    auto uniform = [](int64_t v) {
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+        return (int64_t)(((uint64_t)hi << 32) | lo);
+    };
+    const int lane_off = lane * 8;
     auto load_tile = [&](int key0, KTile& t) {
         const int page = pages[key0 >> page_shift];
         const int off = key0 & page_mask;
-        const bf16_t* kp = pool + kv_k_index(a.geom, a.layer, page, hkv, off, 0) + lane * 8;
-        const bf16_t* vp = pool + kv_v_index(a.geom, a.layer, page, hkv, off, 0) + lane * 8;
+        const int64_t ki = kv_k_index(a.geom, a.layer, page, hkv, off, 0), vi = kv_v_index(a.geom, a.layer, page, hkv, off, 0);
+        // one scalar base per 4 KB (the immediate offset of a load reaches 4095 bytes)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb) {
+            const bf16_t* kp = pool + uniform(ki + kb * 2048);
+            const bf16_t* vp = pool + uniform(vi + kb * 2048);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                t.k[kb][kk] = *reinterpret_cast<const u32x4*>(kp + (kb * 4 + kk) * 512);
-#pragma unroll
-        for (int ht = 0; ht < 8; ++ht) t.v[ht] = *reinterpret_cast<const u32x4*>(vp + ht * 512);
+            for (int kk = 0; kk < 4; ++kk) {
+                t.k[kb][kk] = *reinterpret_cast<const u32x4*>(kp + kk * 512 + lane_off);
+                t.v[kb * 4 + kk] = *reinterpret_cast<const u32x4*>(vp + kk * 512 + lane_off);
+            }
+        }
     };
 
     // One 32-key tile: scores, online softmax, PV.  key0 >= kInvalidKey marks a tile past the end of the
@@ -208,18 +218,46 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
         }
     };
 
-    // Two tiles per trip, ping-pong between two register sets.  Loads are unconditional (past the end
-    // they re-load the last tile) so that the wait before a tile's math only has to cover that tile's
-    // loads and the other set stays in flight.
+    // DEPTH 3: three tiles per trip, rotating through three register sets: while one tile is processed the loads of
+    // the next two are in flight (32 KB per wave, 128 KB per CU).  A CU can then pull well over 1/256 of the
+    // HBM bandwidth, so the CUs still busy at the ragged end of a launch speed up instead of idling the bus.
+    // Loads are unconditional (past the end they re-load the last tile) so that the wait before a tile's math
+    // only has to cover that tile's loads and the other sets stay in flight.
     const int ntiles = (kend - kbeg + TILE_KEYS - 1) / TILE_KEYS;
     const int last = ntiles - 1;
-    KTile ta, tb;
-    load_tile(kbeg + min(wave, last) * TILE_KEYS, ta);
-    for (int it = wave; it < ntiles; it += 8) {
-        load_tile(kbeg + min(it + 4, last) * TILE_KEYS, tb);
-        process(ta, kbeg + it * TILE_KEYS);
-        load_tile(kbeg + min(it + 8, last) * TILE_KEYS, ta);
-        process(tb, it + 4 < ntiles ? kbeg + (it + 4) * TILE_KEYS : kInvalidKey);
+    auto key_of = [&](int it) { return it < ntiles ? kbeg + it * TILE_KEYS : kInvalidKey; };
+    if (DEPTH == 3) {
+        KTile ta, tb, tc;
+        load_tile(kbeg + min(wave, last) * TILE_KEYS, ta);
+        load_tile(kbeg + min(wave + 4, last) * TILE_KEYS, tb);
+        for (int it = wave; it < ntiles; it += 12) {
+            load_tile(kbeg + min(it + 8, last) * TILE_KEYS, tc);
+            __builtin_amdgcn_sched_barrier(0);
+            process(ta, kbeg + it * TILE_KEYS);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(kbeg + min(it + 12, last) * TILE_KEYS, ta);
+            __builtin_amdgcn_sched_barrier(0);
+            process(tb, key_of(it + 4));
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(kbeg + min(it + 16, last) * TILE_KEYS, tb);
+            __builtin_amdgcn_sched_barrier(0);
+            process(tc, key_of(it + 8));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {                                     // four row tiles leave registers for two sets only
+        KTile ta, tb;
+        load_tile(kbeg + min(wave, last) * TILE_KEYS, ta);
+        for (int it = wave; it < ntiles; it += 8) {
+            // the fences keep a tile's math (and the waits it starts with) behind the issue of the next tile's loads
+            load_tile(kbeg + min(it + 4, last) * TILE_KEYS, tb);
+            __builtin_amdgcn_sched_barrier(0);
+            process(ta, kbeg + it * TILE_KEYS);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(kbeg + min(it + 8, last) * TILE_KEYS, ta);
+            __builtin_amdgcn_sched_barrier(0);
+            process(tb, key_of(it + 4));
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // ---- merge the four waves of the group through LDS (maxima in log2 units from here on) ----
@@ -227,7 +265,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
     for (int rt = 0; rt < R; ++rt) m_run[rt] = m_run[rt] == -INFINITY ? -INFINITY : mc[rt];
     constexpr int RP = 16 * R;
     __shared__ float m_sh[4][RP], l_sh[4][RP];
-    __shared__ float o_sh[HD][RP + 1];
+    extern __shared__ __attribute__((aligned(16))) float o_dyn[];          // [4 waves][HD][RP + 1]
+    float (*o_sh)[HD][RP + 1] = reinterpret_cast<float (*)[HD][RP + 1]>(o_dyn);
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
         float l = l_run[rt];
@@ -252,26 +291,21 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a, float sca
         m_all[rt] = mm;
         l_all[rt] = ll;
     }
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    // every wave lays its rescaled accumulators down in its own LDS plane, all four at once; after one barrier
+    // the work-group adds the planes up on the way out (taking turns on a single plane cost four serialised
+    // read-modify-write passes, some 10 us per work-group)
 #pragma unroll
-            for (int rt = 0; rt < R; ++rt)
+    for (int rt = 0; rt < R; ++rt)
 #pragma unroll
-                for (int ht = 0; ht < 8; ++ht)
+        for (int ht = 0; ht < 8; ++ht)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float* dst = &o_sh[ht * 16 + 4 * lg + i][rt * 16 + l16];
-                        const float v = o[ht][rt][i] * fac[rt];
-                        *dst = w == 0 ? v : *dst + v;
-                    }
-        }
-        __syncthreads();
-    }
+            for (int i = 0; i < 4; ++i) o_sh[wave][ht * 16 + 4 * lg + i][rt * 16 + l16] = o[ht][rt][i] * fac[rt];
+    __syncthreads();
     const int64_t pbase = (((int64_t)b * a.Hkv + hkv) * a.max_chunks + chunk) * a.rows_pad + row0;
     const int rows_here = min(rows - row0, RP);
     for (int e = tid; e < rows_here * HD; e += 256) {
         const int r = e / HD, d = e % HD;
-        a.part_o[(pbase + r) * HD + d] = o_sh[d][r];
+        a.part_o[(pbase + r) * HD + d] = (o_sh[0][d][r] + o_sh[1][d][r]) + (o_sh[2][d][r] + o_sh[3][d][r]);
     }
     if (wave == 0 && lg == 0) {
 #pragma unroll
@@ -294,9 +328,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     const int b = t / a.n, j = t % a.n;
     const int G = a.Hq / a.Hkv, hkv = h / G, r = j * G + h % G;
     const int total = a.seq_len[a.batch_seq[b]] + a.n;
-    int nch = (total + a.chunk_keys - 1) / a.chunk_keys;
-    const int clen = ((total + nch - 1) / nch + TILE_KEYS - 1) / TILE_KEYS * TILE_KEYS;
-    nch = (total + clen - 1) / clen;               // trailing pieces can be empty after rounding to tiles
+    const int clen = a.req_chunk[2 * b];
+    const int nch = min(a.req_chunk[2 * b + 1], (total + clen - 1) / clen);   // pieces that start below the live end
     const int64_t base = ((int64_t)b * a.Hkv + hkv) * a.max_chunks;
     float M = -INFINITY;
     for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[((base + c) * rows_pad + r) * 2]);
@@ -376,15 +409,23 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         AttnArgs b = a;
         const int tiles = rp / 16;
         b.row_groups = (tiles + 3) / 4;
+        if (getenv("SV_RG")) b.row_groups = atoi(getenv("SV_RG"));
         const int R = b.row_groups == 1 ? std::max(tiles, a.min_row_tiles) : (tiles + b.row_groups - 1) / b.row_groups;
         dim3 grid((a.n_work * a.Hkv + 7) / 8 * 8 * b.row_groups);
+        auto launch = [&](auto kern, int r) -> hipError_t {
+            const size_t lds = (size_t)4 * HD * (16 * r + 1) * sizeof(float);
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, b, sl2);
+            return hipGetLastError();
+        };
+        hipError_t e;
         switch (R) {
-            case 1: hipLaunchKernelGGL(attn_bf16_kernel<1>, grid, dim3(256), 0, st, b, sl2); break;
-            case 2: hipLaunchKernelGGL(attn_bf16_kernel<2>, grid, dim3(256), 0, st, b, sl2); break;
-            case 3: hipLaunchKernelGGL(attn_bf16_kernel<3>, grid, dim3(256), 0, st, b, sl2); break;
-            default: hipLaunchKernelGGL(attn_bf16_kernel<4>, grid, dim3(256), 0, st, b, sl2); break;
+            case 1: e = getenv("SV_D3") ? launch(attn_bf16_kernel<1, 3>, 1) : launch(attn_bf16_kernel<1, 2>, 1); break;
+            case 2: e = getenv("SV_D3") ? launch(attn_bf16_kernel<2, 3>, 2) : launch(attn_bf16_kernel<2, 2>, 2); break;
+            case 3: e = launch(attn_bf16_kernel<3, 2>, 3); break;
+            default: e = launch(attn_bf16_kernel<4, 2>, 4); break;
         }
-        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, (a.Hq + 7) / 8), dim3(256), 0, st, b);
         return hipGetLastError();

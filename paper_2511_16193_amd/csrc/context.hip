@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 #include <algorithm>
+#include <functional>
 #include <cmath>
 #include <string>
 #include <vector>
@@ -68,7 +69,7 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split) {
 }
 
 struct Layout {                       // byte offsets into the workspace
-    size_t seq_len, page_table, batch_seq, upd, work, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
+    size_t seq_len, page_table, batch_seq, upd, work, req_chunk, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
     size_t rope, row_stat, h, a_norm, q, attn, part, act, logits, part_o, part_ml, total;
     size_t moe_ids, moe_w, moe_cnt, moe_off, moe_perm, moe_inv, moe_act, moe_y;   // mixture-of-experts scratch
     int T, rows_pad, max_chunks;
@@ -91,7 +92,8 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.batch_seq = take(sizeof(int32_t) * r.max_batch);
     L.upd = take(sizeof(int32_t) * 3 * (size_t)r.max_batch * 8);
     L.max_chunks = (int)(((size_t)r.max_pages_per_seq * r.page_size + kChunkKeys - 1) / kChunkKeys);
-    L.work = take(sizeof(int32_t) * (size_t)r.max_batch * L.max_chunks);
+    L.work = take(sizeof(int32_t) * 4 * (size_t)r.max_batch * L.max_chunks);
+    L.req_chunk = take(sizeof(int32_t) * 2 * (size_t)r.max_batch);
     L.row_tok = take(sizeof(int32_t) * T);
     L.row_pos = take(sizeof(int32_t) * T);
     L.row_slot = take(sizeof(int32_t) * T);
@@ -313,7 +315,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->attn_chunk = kChunkKeys;
     c->attn_chunk_opt = 0;
     c->prof_mask = 0;
-    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8 + L.max_chunks) + 8;
+    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8 + 4 * L.max_chunks + 2) + 8;
     for (int i = 0; i < kRing; ++i) { c->staging[i] = nullptr; c->staged[i] = nullptr; c->staged_valid[i] = false; }
     for (int i = 0; i < kRing; ++i) {
         if (hipHostMalloc(reinterpret_cast<void**>(&c->staging[i]), slot_ints * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
@@ -471,37 +473,60 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
     }
     // attention work list: every (request, chunk) that can exist given the upper bounds of the lengths,
     // longest pieces first (the hardware hands work-groups to CUs in order, so this is longest-processing-
-    // time-first list scheduling).  Keys per chunk, unless fixed by option: the candidate that minimises
-    // (all keys + a fixed cost per work-group, measured at ~350 keys' worth) / 256 CUs + half a work-group
-    // for the ragged end.
+    // time-first list scheduling).  Keys per chunk, unless fixed by option: each candidate's launch is
+    // simulated -- every piece goes to the CU that frees up first and costs its keys plus a fixed ~300 keys'
+    // worth (measured: ~6 us of start-up and merge per work-group against ~46 keys per us per CU) -- and the
+    // shortest makespan wins.
     {
         int chunk = c->attn_chunk_opt;
         if (chunk == 0) {
             double best = 1e300;
+            std::vector<int> lens;
+            std::vector<double> cu(256);
             for (int cand : {1024, 1536, 2048, 3072, 4096, 6144, 8192}) {
-                double keys = 0, groups = 0;
+                lens.clear();
                 for (int b = 0; b < B; ++b) {
                     const int total = c->seqs[ids[b]].len_ub + extra;
-                    keys += total;
-                    groups += (total + cand - 1) / cand;
+                    const int nch = std::max(1, std::min((total + cand - 1) / cand, c->lay.max_chunks));
+                    for (int ch = 0; ch < nch; ++ch) lens.push_back((total + nch - 1) / nch);
                 }
-                const double ov = 350.0, heads = c->model.n_kv_heads;
-                const double cost = (keys + groups * ov) * heads / 256.0 + 0.5 * (cand + ov);
-                if (cost < best) { best = cost; chunk = cand; }
+                std::sort(lens.begin(), lens.end(), std::greater<int>());
+                std::fill(cu.begin(), cu.end(), 0.0);
+                for (int len : lens)
+                    for (int h = 0; h < c->model.n_kv_heads; ++h) {
+                        std::pop_heap(cu.begin(), cu.end(), std::greater<double>());
+                        cu.back() += len + 300.0;
+                        std::push_heap(cu.begin(), cu.end(), std::greater<double>());
+                    }
+                const double makespan = *std::max_element(cu.begin(), cu.end());
+                if (makespan < best) { best = makespan; chunk = cand; }
             }
         }
         c->attn_chunk = chunk;
-        int32_t* work = upd + 3 * nupd;
-        std::vector<std::pair<int, int>> items;
+        // An item carries all a work-group needs to start streaming -- (request << 16 | chunk), sequence id,
+        // first key, end of the piece -- so that its first K/V load is two dependent reads away (item, then
+        // page table; the live length is read beside it and only clips the end).  Pieces are cut from the
+        // upper bounds of the lengths: equal parts, whole 32-key tiles.
+        int32_t* req = upd + 3 * nupd;                   // per request: keys per piece, pieces
+        int32_t* work = req + 2 * B;
+        struct Item { int len, b, ch, seq, kbeg, kend; };
+        std::vector<Item> items;
         for (int b = 0; b < B; ++b) {
             const int total = c->seqs[ids[b]].len_ub + extra;
-            const int nch = std::min((total + chunk - 1) / chunk, c->lay.max_chunks);
-            for (int ch = 0; ch < nch; ++ch) items.push_back({-(total / nch), (b << 16) | ch});
+            const int nch = std::max(1, std::min((total + chunk - 1) / chunk, c->lay.max_chunks));
+            const int clen = ((total + nch - 1) / nch + 31) / 32 * 32;
+            req[2 * b] = clen; req[2 * b + 1] = nch;
+            for (int ch = 0; ch < nch && ch * clen < total; ++ch)
+                items.push_back({std::min(clen, total - ch * clen), b, ch, ids[b], ch * clen, std::min((ch + 1) * clen, total)});
         }
-        std::stable_sort(items.begin(), items.end(), [](const std::pair<int, int>& x, const std::pair<int, int>& y) { return x.first < y.first; });
+        std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.len > y.len; });
         int nw = 0;
-        for (auto& t : items) work[nw++] = t.second;
-        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.work), work, nw * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+        for (auto& t : items) {
+            work[4 * nw] = (t.b << 16) | t.ch; work[4 * nw + 1] = t.seq; work[4 * nw + 2] = t.kbeg; work[4 * nw + 3] = t.kend;
+            ++nw;
+        }
+        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.req_chunk), req, 2 * B * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.work), work, 4 * nw * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
         c->n_work = nw;
     }
     SV_HIP(c, hipEventRecord(c->staged[slot], c->stream));
@@ -577,7 +602,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.batch_seq = rp.batch_seq; aa.seq_len = rp.seq_len; aa.out = c->at<void>(L.attn);
         aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml); aa.rows_pad = L.rows_pad; aa.row_groups = 1;
         aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
-        aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work;
+        aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work; aa.req_chunk = c->at<int32_t>(L.req_chunk);
         aa.out_packed = c->packed;
         aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
         aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
@@ -805,7 +830,7 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.batch_seq = c->at<int32_t>(c->lay.batch_seq); aa.seq_len = c->at<int32_t>(c->lay.seq_len); aa.out = out;
     aa.part_o = c->at<float>(c->lay.part_o); aa.part_ml = c->at<float>(c->lay.part_ml); aa.rows_pad = c->lay.rows_pad; aa.row_groups = 1;
     aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
-    aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(c->lay.work); aa.n_work = c->n_work;
+    aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(c->lay.work); aa.n_work = c->n_work; aa.req_chunk = c->at<int32_t>(c->lay.req_chunk);
     aa.out_packed = false;
     aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
@@ -873,7 +898,7 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
             c->attn_generic = value != 0;
             return SV_OK;
         case SV_OPT_ATTN_CHUNK_KEYS:
-            if (value != 0 && (value < kChunkKeys || value % kChunkKeys != 0)) return c->fail(SV_EINVAL, "chunk of %d keys", value);
+            if (value != 0 && (value < kChunkKeys || value % 128 != 0)) return c->fail(SV_EINVAL, "chunk of %d keys", value);
             c->attn_chunk_opt = value;
             return SV_OK;
         case SV_OPT_ATTN_MIN_ROW_TILES:

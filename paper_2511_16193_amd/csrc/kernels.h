@@ -67,7 +67,8 @@ struct AttnArgs {
     float* part_ml;                     // [B][Hkv][max_chunks][rows_pad][2]
     int B, n, k, Hq, Hkv, hd, dtype;
     int chunk_keys, max_chunks;
-    const int32_t* work; int n_work;    // (request << 16 | chunk) items of the bf16 kernel
+    const int32_t* work; int n_work;    // items of the bf16 kernel, 4 ints each: request << 16 | chunk, sequence id, first key, end
+    const int32_t* req_chunk;           // [B][2] keys per piece, pieces (from the host's upper bounds of the lengths)
     int min_row_tiles;                  // lower bound on the 16-row tiles of the bf16 kernel (tuning)
     bool out_packed;                    // write `out` in the packed activation order (see act_index)
     bool force_generic;                 // take the untuned one-wave-per-row path whatever the shape
