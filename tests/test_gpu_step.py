@@ -76,6 +76,7 @@ SMALL_BF16 = W.Shape("small-bf16", 3, 256, 8, 2, 128, 512, 2048, dtype="bf16", b
     (6, 3, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),     # 76 stacked rows per kv head: two row groups of 3 tiles
     (8, 3, OV.GREEDY, 0, True),                          # 100 stacked rows: two row groups of 4 tiles (the 32B
                                                          # configuration's three chains of eight drafts)
+    (-4, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),    # k = 4 with ragged draft windows (0..4 per request)
 ])
 def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed):
     """bf16 decoder small enough for the oracle (3 layers, d 256, 8 q / 2 kv heads x 128, vocab 2048) over a
@@ -85,6 +86,8 @@ def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed)
     streaming order, which selects the weight-streaming projection kernel.
     Drafts come from target-independent q (about half are accepted because random-weight targets are nearly
     flat).  Two consecutive steps: the second runs on the rolled-back cache."""
+    ragged = k < 0          # per-request draft windows: the requests of one launch verify different numbers of drafts
+    k = abs(k)
     shape = W.scaled_down(SMALL_BF16, k=k, n_chains=n_chains)
     lengths = [0, 31, 1024, 2500, 4133]
     B, V = len(lengths), shape.vocab
@@ -112,7 +115,11 @@ def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed)
                     if i < 1 + b % k:
                         drafts[b, (b + step) % n_chains, i] = tok
         u = W.make_uniforms((B, n_chains, k + 1), shape.seed + step)
-        r, g = case.step(x0, drafts, q if vmode == OV.STOCHASTIC else None, u if vmode == OV.STOCHASTIC else None)
+        lens = np.array([(b + step) % (k + 1) for b in range(B)], dtype=np.int64) if ragged else None
+        r, g = case.step(x0, drafts, q if vmode == OV.STOCHASTIC else None, u if vmode == OV.STOCHASTIC else None,
+                         draft_lens=lens)
+        if ragged:
+            assert np.all(g["accepted_len"] <= lens)
         # rows of requests that diverged earlier (exempt decisions) are no longer comparable
         if not alive.all():
             for key in g:
