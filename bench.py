@@ -30,7 +30,11 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the copy-kernel calibration stated there), averaged over the launches of a kind in one step.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/verify_step_cfg2_hbm_traffic.txt: projections (18514 MiB read + 2297 MiB written) / 113 launches;
+    # attention main + merge kernel of one layer (602.5 MiB read + 11.6 MiB written)
+    "cfg2-7b-b64-k4": {"gemm": 193.1e6, "attention": 643.9e6},
+}
 
 
 def log(*a):
