@@ -71,7 +71,7 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split) {
 struct Layout {                       // byte offsets into the workspace
     size_t seq_len, page_table, batch_seq, upd, work, req_chunk, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
     size_t rope, row_stat, h, a_norm, q, attn, part, act, logits, part_o, part_ml, total;
-    size_t moe_ids, moe_w, moe_cnt, moe_off, moe_perm, moe_inv, moe_act, moe_y;   // mixture-of-experts scratch
+    size_t moe_ids, moe_w, moe_cnt, moe_off, moe_perm, moe_inv, moe_act, moe_y, moe_logits;   // mixture-of-experts scratch
     int T, rows_pad, max_chunks;
 };
 
@@ -129,7 +129,7 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.rows_pad = std::max(64, std::min(256, (G * (1 + r.max_chains * r.max_k) + 15) / 16 * 16));
     L.part_o = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * m.head_dim);
     L.part_ml = take(sizeof(float) * (size_t)r.max_batch * m.n_kv_heads * L.max_chunks * L.rows_pad * 2);
-    L.moe_ids = L.moe_w = L.moe_cnt = L.moe_off = L.moe_perm = L.moe_inv = L.moe_act = L.moe_y = 0;
+    L.moe_ids = L.moe_w = L.moe_cnt = L.moe_off = L.moe_perm = L.moe_inv = L.moe_act = L.moe_y = L.moe_logits = 0;
     if (m.n_experts > 0) {
         const size_t tiles = (size_t)moe_max_tiles(T, m.n_experts, m.top_k);
         L.moe_ids = take(sizeof(int32_t) * (size_t)T * m.top_k);
@@ -140,6 +140,7 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
         L.moe_inv = take(sizeof(int32_t) * (size_t)T * m.top_k);
         L.moe_act = take(es * 32 * tiles * m.d_expert);
         L.moe_y = take(sizeof(float) * 32 * tiles * m.d_model);
+        L.moe_logits = take(sizeof(float) * 4 * (size_t)T * m.n_experts);
     }
     L.total = o;
     return true;
@@ -618,7 +619,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
             MoeArgs ma;
             ma.a = (const bf16_t*)a_norm; ma.w_router = (const bf16_t*)c->wrouter[l];
             ma.w_gate_up = (const bf16_t*)c->wgu[l]; ma.w_down = (const bf16_t*)c->wdown[l];
-            ma.top_ids = c->at<int32_t>(L.moe_ids); ma.top_w = c->at<float>(L.moe_w);
+            ma.top_ids = c->at<int32_t>(L.moe_ids); ma.top_w = c->at<float>(L.moe_w); ma.router_logits = c->at<float>(L.moe_logits);
             ma.cnt = c->at<int32_t>(L.moe_cnt); ma.tile_off = c->at<int32_t>(L.moe_off);
             ma.perm = c->at<int32_t>(L.moe_perm); ma.inv = c->at<int32_t>(L.moe_inv);
             ma.act = c->at<bf16_t>(L.moe_act); ma.y = c->at<float>(L.moe_y); ma.out = part;
@@ -767,7 +768,7 @@ extern "C" size_t sv_op_sample_scratch_bytes(int B, int N, int k) {
     return align_up(sizeof(float) * 4 * (size_t)B * (1 + N * k)) + 3 * align_up(sizeof(int32_t) * (size_t)B * N);
 }
 
-struct MoeScratch { size_t ids, w, cnt, off, perm, inv, act, y, total; };
+struct MoeScratch { size_t ids, w, cnt, off, perm, inv, act, y, logits, total; };
 static MoeScratch moe_scratch(int T, int d, int E, int top_k, int F) {
     MoeScratch m;
     size_t o = 0;
@@ -781,6 +782,7 @@ static MoeScratch moe_scratch(int T, int d, int E, int top_k, int F) {
     m.inv = take(sizeof(int32_t) * (size_t)T * top_k);
     m.act = take(sizeof(bf16_t) * 32 * tiles * F);
     m.y = take(sizeof(float) * 32 * tiles * d);
+    m.logits = take(sizeof(float) * 4 * (size_t)T * E);
     m.total = o;
     return m;
 }
@@ -802,6 +804,7 @@ extern "C" int sv_op_moe_ffn(const void* a_packed, const void* w_router, const v
     ma.a = (const bf16_t*)a_packed; ma.w_router = (const bf16_t*)w_router;
     ma.w_gate_up = (const bf16_t*)w_gate_up_packed; ma.w_down = (const bf16_t*)w_down_packed;
     ma.top_ids = reinterpret_cast<int32_t*>(ws + m.ids); ma.top_w = reinterpret_cast<float*>(ws + m.w);
+    ma.router_logits = reinterpret_cast<float*>(ws + m.logits);
     ma.cnt = reinterpret_cast<int32_t*>(ws + m.cnt); ma.tile_off = reinterpret_cast<int32_t*>(ws + m.off);
     ma.perm = reinterpret_cast<int32_t*>(ws + m.perm); ma.inv = reinterpret_cast<int32_t*>(ws + m.inv);
     ma.act = reinterpret_cast<bf16_t*>(ws + m.act); ma.y = reinterpret_cast<float*>(ws + m.y); ma.out = out;

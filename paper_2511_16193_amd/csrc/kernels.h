@@ -82,6 +82,7 @@ struct MoeArgs {
     const bf16_t* w_router;   // [E][d] row-major
     const bf16_t* w_gate_up;  // [E][2F][d] packed as one (E*2F) x d matrix
     const bf16_t* w_down;     // [E][d][F] packed as one (E*d) x F matrix
+    float* router_logits;     // [4][T][E] partial router logits (up to four parts of the reduction)
     int32_t* top_ids;         // [T][top_k] experts in descending probability
     float* top_w;             // [T][top_k] renormalised weights
     int32_t* cnt;             // [E] rows per expert

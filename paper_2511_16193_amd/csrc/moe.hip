@@ -18,48 +18,84 @@ namespace sv {
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 // ------------------------------------------------------------------ router
-// Four rows per work-group: the rows sit in LDS, each wave takes a quarter of the experts, the lanes of a wave
-// split the reduction of one expert's dot products and add their parts up in a fixed order.  Then one wave per
-// row: softmax over the experts, top_k by repeated arg-max (lowest id among equals), renormalisation.
-constexpr int kRouterRows = 4;
+// Logits by MFMA (v_mfma_f32_32x32x16_bf16).  A work-group takes 32 rows and one of KQ parts of the reduction;
+// each of its four waves covers a quarter of that part for all ET = E/32 expert tiles -- expert rows as the
+// first operand straight from the row-major router matrix, the activation fragment straight from the packed
+// activations (1 KB contiguous), four slices of loads in flight ahead of the products.  The waves' partial
+// logits meet in LDS and leave as one plane [part][row][expert] in global memory.
+constexpr int kRouterRows = 32;
 
-__global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
+template <int ET>
+__global__ __launch_bounds__(256) void moe_logits_kernel(MoeArgs a, int KQ) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* rows = reinterpret_cast<bf16_t*>(smem);                                 // [4][d]
-    float* logit = reinterpret_cast<float*>(smem + (size_t)kRouterRows * a.d * 2);  // [4][E]
-    const int t0 = blockIdx.x * kRouterRows;
+    float* logit = reinterpret_cast<float*>(smem);           // [4 waves][32][E + 1]
+    const int pitch = a.E + 1, plane = kRouterRows * pitch;
+    const int tile = blockIdx.x, kq = blockIdx.y;            // 32-row tile of the packed activations, part of the reduction
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int pieces = a.d / 8;
-    for (int i = threadIdx.x; i < kRouterRows * pieces; i += 256) {
-        const int r = i / pieces, p = i % pieces;
-        const int t = t0 + r < a.T ? t0 + r : a.T - 1;
-        *reinterpret_cast<u32x4*>(rows + (size_t)r * a.d + 8 * p) =
-            *reinterpret_cast<const u32x4*>(a.a + act_index(t, 8 * p, a.d, true));
-    }
-    __syncthreads();
-    for (int e = wave; e < a.E; e += 4) {
-        float acc[kRouterRows] = {0.f, 0.f, 0.f, 0.f};
-        const bf16_t* w = a.w_router + (size_t)e * a.d;
-        for (int p = lane; p < pieces; p += 64) {
-            const u32x4 wv = *reinterpret_cast<const u32x4*>(w + 8 * p);
+    const int l32 = lane & 31, lg = lane >> 5;
+    const int kslices = a.d / 16, nks = kslices / (4 * KQ), ks0 = (kq * 4 + wave) * nks;
+    const bf16_t* a_src = a.a + ((int64_t)tile * kslices + ks0) * 512 + lane * 8;
+    const bf16_t* w_src = a.w_router + (int64_t)l32 * a.d + ks0 * 16 + 8 * lg;
+    constexpr int GS = 4;
+    floatx16 acc[ET];
 #pragma unroll
-            for (int r = 0; r < kRouterRows; ++r) {
-                const u32x4 xv = *reinterpret_cast<const u32x4*>(rows + (size_t)r * a.d + 8 * p);
+    for (int et = 0; et < ET; ++et)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    acc[r] = fmaf(__uint_as_float(wv[j] << 16), __uint_as_float(xv[j] << 16), acc[r]);
-                    acc[r] = fmaf(__uint_as_float(wv[j] & 0xffff0000u), __uint_as_float(xv[j] & 0xffff0000u), acc[r]);
-                }
-            }
+        for (int q = 0; q < 16; ++q) acc[et][q] = 0.f;
+    u32x4 xa[2][GS], wa[2][GS][ET];
+    auto load_group = [&](int g, u32x4 (&x)[GS], u32x4 (&w)[GS][ET]) {
+#pragma unroll
+        for (int s_ = 0; s_ < GS; ++s_) {
+            const int ks = g * GS + s_;
+            const bool ok = ks < nks;
+            const int kc = ok ? ks : nks - 1;
+            const u32x4 xv = *reinterpret_cast<const u32x4*>(a_src + (int64_t)kc * 512);
+            x[s_] = ok ? xv : u32x4{0, 0, 0, 0};                // a slice past the end contributes nothing
+#pragma unroll
+            for (int et = 0; et < ET; ++et) w[s_][et] = *reinterpret_cast<const u32x4*>(w_src + (int64_t)et * 32 * a.d + kc * 16);
         }
+    };
+    auto mma_group = [&](const u32x4 (&x)[GS], const u32x4 (&w)[GS][ET]) {
 #pragma unroll
-        for (int r = 0; r < kRouterRows; ++r) {
-            const float s = wave_sum(acc[r]);
-            if (lane == 0) logit[r * a.E + e] = s;
-        }
+        for (int s_ = 0; s_ < GS; ++s_)
+#pragma unroll
+            for (int et = 0; et < ET; ++et)
+                acc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w[s_][et]),
+                                                                 __builtin_bit_cast(bf16x8, x[s_]), acc[et], 0, 0, 0);
+    };
+    const int ngroups = (nks + GS - 1) / GS;
+    load_group(0, xa[0], wa[0]);
+    for (int g = 0; g < ngroups; g += 2) {
+        load_group(g + 1, xa[1], wa[1]);                       // past the end: zero activations
+        __builtin_amdgcn_sched_barrier(0);
+        mma_group(xa[0], wa[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_group(g + 2, xa[0], wa[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_group(xa[1], wa[1]);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    // acc[et][4 q + i] <-> expert et*32 + 8 q + 4 lg + i, row l32
+#pragma unroll
+    for (int et = 0; et < ET; ++et)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) logit[wave * plane + l32 * pitch + et * 32 + 8 * q + 4 * lg + i] = acc[et][4 * q + i];
     __syncthreads();
-    const int t = t0 + wave;
+    float* dst = a.router_logits + ((int64_t)kq * a.T + (int64_t)tile * 32) * a.E;
+    for (int i = threadIdx.x; i < kRouterRows * a.E; i += 256) {
+        const int r = i / a.E, e = i % a.E;
+        if (tile * 32 + r < a.T)
+            dst[(int64_t)r * a.E + e] = (logit[r * pitch + e] + logit[plane + r * pitch + e]) + (logit[2 * plane + r * pitch + e] + logit[3 * plane + r * pitch + e]);
+    }
+}
+
+// One wave per row: the KQ planes are added in order, softmax over the experts, top_k by repeated arg-max
+// (lowest id among equals), renormalisation.
+__global__ __launch_bounds__(256) void moe_select_kernel(MoeArgs a, int KQ) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= a.T) return;
     constexpr int PER = 4;                                   // experts per lane: E <= 256
     float v[PER];
@@ -67,8 +103,13 @@ __global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int e = lane + 64 * i;
-        v[i] = e < a.E ? logit[wave * a.E + e] : -INFINITY;
-        mx = fmaxf(mx, v[i]);
+        float x = -INFINITY;
+        if (e < a.E) {
+            x = 0.f;
+            for (int kq = 0; kq < KQ; ++kq) x += a.router_logits[((int64_t)kq * a.T + t) * a.E + e];
+        }
+        v[i] = x;
+        mx = fmaxf(mx, x);
     }
     mx = wave_max(mx);
     float sum = 0.f;
@@ -321,10 +362,9 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(MoeArgs a) {
 
 int moe_shape_ok(int T, int d, int E, int top_k, int F) {
     if (T <= 0 || d <= 0 || E <= 0 || top_k <= 0 || F <= 0) return 0;
-    if (E % 64 != 0 || E > 256 || top_k > E || top_k > 64) return 0;       // router: four experts per lane, top_k <= lanes
+    if (E % 64 != 0 || E > 256 || top_k > E || top_k > 64) return 0;       // router: 32-expert MFMA tiles, four experts per lane, top_k <= lanes
     if (d % 128 != 0 || F % 128 != 0) return 0;                            // eight 16-wide slices per fill; 128-feature strips
-    if (moe_group_lds_bytes(T, E) > 150 * 1024) return 0;
-    if ((size_t)kRouterRows * d * 2 + (size_t)kRouterRows * E * 4 > 150 * 1024) return 0;
+    if (moe_group_lds_bytes(T, E) > 150 * 1024 || (size_t)4 * kRouterRows * (E + 1) * 4 > 150 * 1024) return 0;
     return 1;
 }
 
@@ -340,14 +380,28 @@ hipError_t moe_ffn(const MoeArgs& a, hipStream_t st) {
     if (!attr_set) {
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(moe_group_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(moe_router_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e1 != hipSuccess) return e1;
-        if (e2 != hipSuccess) return e2;
+        for (const void* k : {reinterpret_cast<const void*>(moe_logits_kernel<2>), reinterpret_cast<const void*>(moe_logits_kernel<4>),
+                              reinterpret_cast<const void*>(moe_logits_kernel<6>), reinterpret_cast<const void*>(moe_logits_kernel<8>)}) {
+            hipError_t e2 = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+            if (e2 != hipSuccess) return e2;
+        }
         attr_set = true;
     }
-    const size_t router_lds = (size_t)kRouterRows * a.d * 2 + (size_t)kRouterRows * a.E * 4;
-    hipLaunchKernelGGL(moe_router_kernel, dim3((a.T + kRouterRows - 1) / kRouterRows), dim3(256), router_lds, st, a);
+    // parts of the router's reduction: as many as leave every wave at least two 16-wide slices, at most four
+    const int kslices = a.d / 16;
+    int KQ = 4;
+    while (KQ > 1 && (kslices % (4 * KQ) != 0 || kslices / (4 * KQ) < 2)) KQ >>= 1;
+    const size_t router_lds = (size_t)4 * kRouterRows * (a.E + 1) * 4;
+    const dim3 rgrid((a.T + kRouterRows - 1) / kRouterRows, KQ);
+    switch (a.E / 32) {
+        case 2: hipLaunchKernelGGL(moe_logits_kernel<2>, rgrid, dim3(256), router_lds, st, a, KQ); break;
+        case 4: hipLaunchKernelGGL(moe_logits_kernel<4>, rgrid, dim3(256), router_lds, st, a, KQ); break;
+        case 6: hipLaunchKernelGGL(moe_logits_kernel<6>, rgrid, dim3(256), router_lds, st, a, KQ); break;
+        case 8: hipLaunchKernelGGL(moe_logits_kernel<8>, rgrid, dim3(256), router_lds, st, a, KQ); break;
+        default: return hipErrorInvalidValue;
+    }
+    hipLaunchKernelGGL(moe_select_kernel, dim3((a.T + 3) / 4), dim3(256), 0, st, a, KQ);
     hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(1024), moe_group_lds_bytes(a.T, a.E), st, a);
     hipLaunchKernelGGL(moe_gemm_kernel<0>, dim3(a.E * (a.F / 64)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(moe_gemm_kernel<1>, dim3(a.E * (a.d / 128)), dim3(256), 0, st, a);

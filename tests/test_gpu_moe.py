@@ -62,8 +62,10 @@ def test_moe_ffn_matches_oracle(T, d, E, top_k, F, skew):
     for t in np.nonzero(clear)[0]:
         assert set(ids[t]) == set(ids_o[t]), f"row {t}: {ids[t]} vs {ids_o[t]} (margin {margin[t]})"
         got = dict(zip(ids[t], wts[t]))
+        # logits of magnitude ~10 summed in fp32 over d products carry ~1e-5 absolute error, which is the
+        # relative error of the probabilities
         for e, w in zip(ids_o[t], wts_o[t]):
-            assert abs(got[e] - w) < 1e-5
+            assert abs(got[e] - w) < 5e-5
     assert np.all(np.abs(wts.sum(axis=1) - 1.0) < 1e-5)
     if skew:
         counts = np.bincount(ids_o.reshape(-1), minlength=E)
