@@ -69,7 +69,7 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split) {
 }
 
 struct Layout {                       // byte offsets into the workspace
-    size_t seq_len, page_table, batch_seq, upd, work, req_chunk, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row;
+    size_t seq_len, page_table, batch_seq, upd, work, req_chunk, row_tok, row_pos, row_slot, chain_acc, chain_tok, chain_row, draw_part;
     size_t rope, row_stat, h, a_norm, q, attn, part, act, logits, part_o, part_ml, total;
     size_t moe_ids, moe_w, moe_cnt, moe_off, moe_perm, moe_inv, moe_act, moe_y, moe_logits;   // mixture-of-experts scratch
     int T, rows_pad, max_chunks;
@@ -100,6 +100,7 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.chain_acc = take(sizeof(int32_t) * r.max_batch * r.max_chains);
     L.chain_tok = take(sizeof(int32_t) * r.max_batch * r.max_chains);
     L.chain_row = take(sizeof(int32_t) * r.max_batch * r.max_chains);
+    L.draw_part = take(sizeof(float) * 4 * kDrawParts * r.max_batch * r.max_chains);
     L.rope = take(sizeof(float) * (size_t)T * m.head_dim);
     L.row_stat = take(sizeof(float) * 4 * T);
     L.h = take(sizeof(float) * (size_t)T * m.d_model);
@@ -688,7 +689,7 @@ extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts,
     SampleArgs sa;
     sa.logits = c->at<float>(L.logits); sa.drafts = drafts; sa.draft_probs = draft_probs; sa.uniforms = uniforms;
     sa.draft_lens = bt->draft_lens; sa.row_stat = c->at<float>(L.row_stat);
-    sa.chain_acc = c->at<int32_t>(L.chain_acc); sa.chain_tok = c->at<int32_t>(L.chain_tok); sa.chain_row = c->at<int32_t>(L.chain_row);
+    sa.chain_acc = c->at<int32_t>(L.chain_acc); sa.chain_tok = c->at<int32_t>(L.chain_tok); sa.chain_row = c->at<int32_t>(L.chain_row); sa.draw_part = c->at<float>(L.draw_part);
     sa.accepted_len = out->accepted_len; sa.out_tokens = out->out_tokens; sa.best_chain = out->best_chain;
     sa.B = B; sa.N = N; sa.k = k; sa.V = c->model.vocab; sa.verify_mode = c->rt.verify_mode; sa.sample_mode = c->rt.sample_mode;
     sa.temperature = c->rt.temperature;
@@ -757,7 +758,8 @@ extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const fl
     sa.row_stat = reinterpret_cast<float*>(p); p += align_up(sizeof(float) * 4 * T);
     sa.chain_acc = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * S);
     sa.chain_tok = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * S);
-    sa.chain_row = reinterpret_cast<int32_t*>(p);
+    sa.chain_row = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * S);
+    sa.draw_part = reinterpret_cast<float*>(p);
     sa.accepted_len = accepted_len; sa.out_tokens = out_tokens; sa.best_chain = best_chain;
     sa.B = B; sa.N = N; sa.k = k; sa.V = V; sa.verify_mode = verify_mode; sa.sample_mode = sample_mode; sa.temperature = temperature;
     return sample_verify(sa, (hipStream_t)stream) == hipSuccess ? SV_OK : SV_EHIP;
@@ -765,7 +767,8 @@ extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const fl
 
 extern "C" size_t sv_op_sample_scratch_bytes(int B, int N, int k) {
     if (B <= 0 || N <= 0 || k < 0) return 0;
-    return align_up(sizeof(float) * 4 * (size_t)B * (1 + N * k)) + 3 * align_up(sizeof(int32_t) * (size_t)B * N);
+    return align_up(sizeof(float) * 4 * (size_t)B * (1 + N * k)) + 3 * align_up(sizeof(int32_t) * (size_t)B * N) +
+           align_up(sizeof(float) * 4 * kDrawParts * (size_t)B * N);
 }
 
 struct MoeScratch { size_t ids, w, cnt, off, perm, inv, act, y, logits, total; };

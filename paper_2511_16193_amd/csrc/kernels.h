@@ -110,12 +110,14 @@ struct SampleArgs {
     int32_t* chain_acc;                 // [B][N]
     int32_t* chain_tok;                 // [B][N]
     int32_t* chain_row;                 // [B][N] scratch
+    float* draw_part;                   // [B][N][kDrawParts][4] winners of the parts of the exponential race
     int32_t* accepted_len;              // [B]
     int32_t* out_tokens;                // [B][k+1]
     int32_t* best_chain;                // [B]
     int B, N, k, V, verify_mode, sample_mode;
     float temperature;
 };
+constexpr int kDrawParts = 8;
 hipError_t sample_verify(const SampleArgs& a, hipStream_t st);
 struct RollbackArgs {
     void* pool; KvGeom geom; int n_layers, dtype;

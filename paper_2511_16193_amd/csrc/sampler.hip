@@ -132,7 +132,10 @@ __global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
         const uint64_t key = ((uint64_t)(uint32_t)s << 32) | (uint64_t)__float_as_uint(u);
         float best_r = -INFINITY, best_p = -INFINITY;
         int arg_r = 0x7fffffff, arg_p = 0x7fffffff;
-        for (int v = threadIdx.x; v < V; v += NT) {
+        // the vocabulary is cut into gridDim.y contiguous parts; each work-group finds the winners of its part
+        const int part = (V + gridDim.y - 1) / gridDim.y;
+        const int vbeg = blockIdx.y * part, vend = min(V, vbeg + part);
+        for (int v = vbeg + threadIdx.x; v < vend; v += NT) {
             const uint64_t z = splitmix_finalise(key + (uint64_t)(v + 1) * 0x9E3779B97F4A7C15ull);
             const float U = ((float)(uint32_t)(z >> 32) + 0.5f) * 2.3283064365386963e-10f;
             const float ln_e = logf(-log1pf(-U));
@@ -167,7 +170,8 @@ __global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
                 take(best_r, arg_r, sh_r[w], sh_ar[w]);
                 take(best_p, arg_p, sh_p[w], sh_ap[w]);
             }
-            a.chain_tok[s] = (rejected && best_r > -INFINITY) ? arg_r : arg_p;
+            float* out = a.draw_part + ((int64_t)s * gridDim.y + blockIdx.y) * 4;
+            out[0] = best_r; out[1] = __int_as_float(arg_r); out[2] = best_p; out[3] = __int_as_float(arg_p);
         }
         return;
     }
@@ -261,11 +265,37 @@ __global__ void commit_len_kernel(RollbackArgs r) {
     if (b < r.B) r.seq_len[r.batch_seq[b]] += r.accepted_len[b] + 1;
 }
 
+// Winner of a chain's exponential race over the parts of the vocabulary (larger score; lower id among equals).
+__global__ void draw_reduce_kernel(SampleArgs a, int parts) {
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= a.B * a.N) return;
+    const int b = s / a.N;
+    const int klim = a.draft_lens ? min(a.draft_lens[b], a.k) : a.k;
+    const bool rejected = a.chain_acc[s] < klim;
+    float best_r = -INFINITY, best_p = -INFINITY;
+    int arg_r = 0x7fffffff, arg_p = 0x7fffffff;
+    for (int i = 0; i < parts; ++i) {
+        const float* in = a.draw_part + ((int64_t)s * parts + i) * 4;
+        const float r = in[0], p = in[2];
+        const int ar = __float_as_int(in[1]), ap = __float_as_int(in[3]);
+        if (r > best_r || (r == best_r && ar < arg_r)) { best_r = r; arg_r = ar; }
+        if (p > best_p || (p == best_p && ap < arg_p)) { best_p = p; arg_p = ap; }
+    }
+    a.chain_tok[s] = (rejected && best_r > -INFINITY) ? arg_r : arg_p;
+}
+
 hipError_t sample_verify(const SampleArgs& a, hipStream_t st) {
     const int T = a.B * (1 + a.N * a.k), S = a.B * a.N;
     hipLaunchKernelGGL(row_stats_kernel, dim3(T), dim3(NT), 0, st, a.logits, a.row_stat, a.V, 1.0f / a.temperature);
     hipLaunchKernelGGL(accept_kernel, dim3((S + 63) / 64), dim3(64), 0, st, a);
-    if (a.verify_mode != 0) hipLaunchKernelGGL(draw_kernel, dim3(S), dim3(NT), 0, st, a);
+    if (a.verify_mode != 0) {
+        if (a.sample_mode == 1) {      // the race's per-id arithmetic dominates: spread every chain over several work-groups
+            hipLaunchKernelGGL(draw_kernel, dim3(S, kDrawParts), dim3(NT), 0, st, a);
+            hipLaunchKernelGGL(draw_reduce_kernel, dim3((S + 63) / 64), dim3(64), 0, st, a, kDrawParts);
+        } else {
+            hipLaunchKernelGGL(draw_kernel, dim3(S), dim3(NT), 0, st, a);
+        }
+    }
     hipLaunchKernelGGL(select_kernel, dim3((a.B + 63) / 64), dim3(64), 0, st, a);
     return hipGetLastError();
 }
