@@ -292,10 +292,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(
 // wave needs, go through LDS: KA 16-wide slices of all MT 32-token tiles per fill (packed order too, so
 // a fill is a handful of contiguous 1 KB copies), double buffered, one barrier per fill.
 template <int MT, int NT, int KA, int PD, bool GLU = false>
-__global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void gemm_bf16_ws_kernel(
+__global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_ws_kernel(
     const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
-    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n) {
-    static_assert(!GLU || NT == 1, "the gated form pairs two half strips");
+    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n, int tn0) {
     constexpr int BM = 32 * MT, BN = 128 * NT;
     constexpr int AFR = MT * KA;                          // activation fragments per fill
     static_assert(AFR % 4 == 0, "fill must split over 4 waves");
@@ -307,7 +306,7 @@ __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void gemm_bf16_ws_kernel(
     const int tm = logical % tiles_m;
     logical /= tiles_m;
     const int sp = logical % splits;
-    const int tn = logical / splits;
+    const int tn = tn0 + logical / splits;
     const int m0 = tm * BM, n0 = tn * BN;
     const int ks0 = sp * (k_per_split / 16);              // first 16-wide slice of this split
     const int nfill = k_per_split / (16 * KA);
@@ -331,9 +330,13 @@ __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void gemm_bf16_ws_kernel(
     const bf16_t* w_src[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-        // gated form (N = 2F weight rows, gate rows first): work-group tn covers features 64 tn .. 64 tn + 63;
-        // waves 0,1 stream their gate rows, waves 2,3 the up rows of the same features
-        const int nt = GLU ? (wave < 2 ? 2 * tn + wave : N / 64 + 2 * tn + (wave - 2)) : n0 / 32 + wave * NT + i;
+        // gated form (N = 2F weight rows, gate rows first).  NT == 1: work-group tn covers features
+        // 64 tn .. 64 tn + 63; waves 0,1 stream their gate rows, waves 2,3 the up rows of the same features.
+        // NT == 2: work-group tn covers features 128 tn .. 128 tn + 127; every wave streams the gate rows (i = 0)
+        // and the up rows (i = 1) of its own 32 features.
+        const int nt = !GLU ? n0 / 32 + wave * NT + i
+                     : NT == 1 ? (wave < 2 ? 2 * tn + wave : N / 64 + 2 * tn + (wave - 2))
+                               : (i == 0 ? 4 * tn + wave : N / 64 + 4 * tn + wave);
         w_src[i] = Wp + (((int64_t)(nt >> 2) * kslices + ks0) * 4 + (nt & 3)) * 512 + lane * 8;
     }
     constexpr int W_STEP = 4 * 512;                       // elements between consecutive slices of a tile
@@ -409,6 +412,32 @@ __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void gemm_bf16_ws_kernel(
             *reinterpret_cast<u32x4*>(&abuf[(fill + 1) & 1][(wave * APW + i) * 1024 + lane * 16]) = areg[i];
     }
 
+    if (GLU && NT == 2) {
+        // gate and up of a feature sit in the same lane: silu(gate) * up in registers, rounded to bf16, written as
+        // packed operand tiles [M/32][F/16][64][8] of the next projection
+        const int F = N / 2;
+        bf16_t* act = reinterpret_cast<bf16_t*>(out);
+        const int fs = (tn * 128 + wave * 32) / 16;
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+            const int mt = m0 / 32 + j;
+            if (mt < m_tiles_total) {
+                bf16_t* dst = act + ((int64_t)mt * (F / 16) + fs) * 512;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float r[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float g = acc[0][j][4 * q + i];
+                        r[i] = g / (1.0f + expf(-g)) * acc[NT - 1][j][4 * q + i];
+                    }
+                    u32x2 pk = {pack2bf(r[0], r[1]), pack2bf(r[2], r[3])};
+                    *reinterpret_cast<u32x2*>(dst + ((q >> 1) * 64 + l32 + 32 * (q & 1)) * 8 + 4 * lg) = pk;
+                }
+            }
+        }
+        return;
+    }
     if (GLU) {
         // up halves travel through LDS to the waves that hold the gate halves; those write
         // silu(gate) * up, rounded to bf16, as packed operand tiles [M/32][F/16][64][8] of the next projection
@@ -494,7 +523,7 @@ static hipError_t launch_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int 
     if (N % BN != 0 || (K / splits) % (16 * KA) != 0) return hipErrorInvalidValue;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     hipLaunchKernelGGL((gemm_bf16_ws_kernel<MT, NT, KA, PD>), dim3(tiles_m * tiles_n * splits), dim3(256), 0, st, Ap, Wp,
-                       out, M, N, K, K / splits, splits, tiles_m, tiles_n);
+                       out, M, N, K, K / splits, splits, tiles_m, tiles_n, 0);
     return hipGetLastError();
 }
 
@@ -502,13 +531,32 @@ static hipError_t launch_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int 
 // [ceil(M/32)*32, F] bf16.  F a multiple of 64.
 hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st) {
     if (F % 64 != 0 || K % 64 != 0) return hipErrorInvalidValue;
+    float* out = reinterpret_cast<float*>(act_out);
+    if (F % 128 == 0 && K % 128 == 0) {
+        // 128-feature strips, gate and up in one wave.  One work-group per CU: the launch runs in rounds of 256,
+        // and a last round that is less than half full would leave most CUs idle for a whole work-group's time.
+        // Its strips are then given to a second launch of 32-row work-groups (five times as many, a fifth as long).
+        const int tiles_m = (M + 159) / 160, strips = F / 128;
+        const int rem = (strips * tiles_m) % 256;
+        const int strips_tail = rem > 0 && rem <= 128 ? (rem + tiles_m - 1) / tiles_m : 0;
+        const int strips_main = strips - strips_tail;
+        if (strips_main > 0)
+            hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 2, 8, 8, true>), dim3(tiles_m * strips_main), dim3(256), 0, st, Ap, Wp,
+                               out, M, 2 * F, K, K, 1, tiles_m, strips_main, 0);
+        if (strips_tail > 0) {
+            const int tiles_m1 = (M + 31) / 32;
+            hipLaunchKernelGGL((gemm_bf16_ws_kernel<1, 2, 8, 8, true>), dim3(tiles_m1 * strips_tail), dim3(256), 0, st, Ap, Wp,
+                               out, M, 2 * F, K, K, 1, tiles_m1, strips_tail, strips_main);
+        }
+        return hipGetLastError();
+    }
     const int tiles_m = (M + 159) / 160, tiles_n = F / 64;
     if (K % 128 == 0)
         hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 1, 8, 8, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, Ap, Wp,
-                           reinterpret_cast<float*>(act_out), M, 2 * F, K, K, 1, tiles_m, tiles_n);
+                           out, M, 2 * F, K, K, 1, tiles_m, tiles_n, 0);
     else
         hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 1, 4, 4, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, Ap, Wp,
-                           reinterpret_cast<float*>(act_out), M, 2 * F, K, K, 1, tiles_m, tiles_n);
+                           out, M, 2 * F, K, K, 1, tiles_m, tiles_n, 0);
     return hipGetLastError();
 }
 
