@@ -28,7 +28,7 @@ constexpr int TILE_KEYS = 32;
 
 struct KTile { u32x4 k[2][4]; u32x4 v[8]; };
 
-template <int R, int DEPTH>
+template <int R>
 __global__ __launch_bounds__(256, R == 1 ? 2 : 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
     // work item = one piece of one request's keys, cut by the host from its upper bounds of the lengths.
     // Launch order: the kv heads of an item are neighbours, so the list's longest-first order holds chip-wide.
@@ -218,33 +218,15 @@ __global__ __launch_bounds__(256, R == 1 ? 2 : 1) void attn_bf16_kernel(AttnArgs
         }
     };
 
-    // DEPTH 3: three tiles per trip, rotating through three register sets: while one tile is processed the loads of
-    // the next two are in flight (32 KB per wave, 128 KB per CU).  A CU can then pull well over 1/256 of the
-    // HBM bandwidth, so the CUs still busy at the ragged end of a launch speed up instead of idling the bus.
+    // Two tiles per trip, ping-pong between two register sets: while one tile is processed the loads of the next
+    // are in flight.  (A third set in flight was measured and does not pay: per tile the wave is bound by its own
+    // instruction issue -- 96 MFMAs plus the softmax arithmetic at three row tiles -- not by the load latency.)
     // Loads are unconditional (past the end they re-load the last tile) so that the wait before a tile's math
-    // only has to cover that tile's loads and the other sets stay in flight.
+    // only has to cover that tile's loads and the other set stays in flight.
     const int ntiles = (kend - kbeg + TILE_KEYS - 1) / TILE_KEYS;
     const int last = ntiles - 1;
     auto key_of = [&](int it) { return it < ntiles ? kbeg + it * TILE_KEYS : kInvalidKey; };
-    if (DEPTH == 3) {
-        KTile ta, tb, tc;
-        load_tile(kbeg + min(wave, last) * TILE_KEYS, ta);
-        load_tile(kbeg + min(wave + 4, last) * TILE_KEYS, tb);
-        for (int it = wave; it < ntiles; it += 12) {
-            load_tile(kbeg + min(it + 8, last) * TILE_KEYS, tc);
-            __builtin_amdgcn_sched_barrier(0);
-            process(ta, kbeg + it * TILE_KEYS);
-            __builtin_amdgcn_sched_barrier(0);
-            load_tile(kbeg + min(it + 12, last) * TILE_KEYS, ta);
-            __builtin_amdgcn_sched_barrier(0);
-            process(tb, key_of(it + 4));
-            __builtin_amdgcn_sched_barrier(0);
-            load_tile(kbeg + min(it + 16, last) * TILE_KEYS, tb);
-            __builtin_amdgcn_sched_barrier(0);
-            process(tc, key_of(it + 8));
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    } else {                                     // four row tiles leave registers for two sets only
+    {
         KTile ta, tb;
         load_tile(kbeg + min(wave, last) * TILE_KEYS, ta);
         for (int it = wave; it < ntiles; it += 8) {
@@ -409,7 +391,6 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         AttnArgs b = a;
         const int tiles = rp / 16;
         b.row_groups = (tiles + 3) / 4;
-        if (getenv("SV_RG")) b.row_groups = atoi(getenv("SV_RG"));
         const int R = b.row_groups == 1 ? std::max(tiles, a.min_row_tiles) : (tiles + b.row_groups - 1) / b.row_groups;
         dim3 grid((a.n_work * a.Hkv + 7) / 8 * 8 * b.row_groups);
         auto launch = [&](auto kern, int r) -> hipError_t {
@@ -421,10 +402,10 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         };
         hipError_t e;
         switch (R) {
-            case 1: e = getenv("SV_D3") ? launch(attn_bf16_kernel<1, 3>, 1) : launch(attn_bf16_kernel<1, 2>, 1); break;
-            case 2: e = getenv("SV_D3") ? launch(attn_bf16_kernel<2, 3>, 2) : launch(attn_bf16_kernel<2, 2>, 2); break;
-            case 3: e = launch(attn_bf16_kernel<3, 2>, 3); break;
-            default: e = launch(attn_bf16_kernel<4, 2>, 4); break;
+            case 1: e = launch(attn_bf16_kernel<1>, 1); break;
+            case 2: e = launch(attn_bf16_kernel<2>, 2); break;
+            case 3: e = launch(attn_bf16_kernel<3>, 3); break;
+            default: e = launch(attn_bf16_kernel<4>, 4); break;
         }
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(attn_merge_kernel, dim3(a.B * a.n, (a.Hq + 7) / 8), dim3(256), 0, st, b);
