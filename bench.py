@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=16, help="requests in the oracle sample (0 = skip)")
     ap.add_argument("--gemm-variant", type=int, default=None)
     ap.add_argument("--attn-chunk", type=int, default=None, help="keys per split-KV chunk (tuning)")
+    ap.add_argument("--attn-max-row-tiles", type=int, default=None, help="16-row tiles per attention work-group (tuning)")
     ap.add_argument("--drafts", choices=["noisy-target", "independent"], default="noisy-target",
                     help="independent: drafts from q = softmax(N(0,1)) without any device decoding step, so that "
                          "every kernel launch of the process has the timed step's shape (used for profiles)")
@@ -140,6 +141,8 @@ def main():
         case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
     if args.attn_chunk is not None:
         case.ver.set_option(P.SV_OPT_ATTN_CHUNK_KEYS, args.attn_chunk)
+    if args.attn_max_row_tiles is not None:
+        case.ver.set_option(P.SV_OPT_ATTN_MAX_ROW_TILES, args.attn_max_row_tiles)
     if args.drafts == "independent":
         log("drafting (target-independent q) ...")
         case.independent_drafts(1.0)

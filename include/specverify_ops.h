@@ -91,9 +91,12 @@ int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launch
  *   SV_OPT_GEMM_VARIANT  kernel / work-group tile of the bf16 projections (0..6; -1 = per shape, default)
  *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)
  *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for
+ *   SV_OPT_ATTN_MAX_ROW_TILES  most 16-row tiles (1..4, default 3) one work-group of the bf16 attention takes;
+ *                           more stacked rows are split over row groups that stream the same keys
  *   SV_OPT_ATTN_CHUNK_KEYS  keys per split-KV chunk of the bf16 attention (multiple of 128, at least 1024; 0 = chosen per
  *                           batch from the lengths, default) */
-enum { SV_OPT_GEMM_VARIANT = 1, SV_OPT_ATTN_GENERIC = 2, SV_OPT_ATTN_MIN_ROW_TILES = 3, SV_OPT_ATTN_CHUNK_KEYS = 4 };
+enum { SV_OPT_GEMM_VARIANT = 1, SV_OPT_ATTN_GENERIC = 2, SV_OPT_ATTN_MIN_ROW_TILES = 3, SV_OPT_ATTN_CHUNK_KEYS = 4,
+       SV_OPT_ATTN_MAX_ROW_TILES = 5 };
 int sv_set_option(sv_ctx *, int option, int value);
 
 #ifdef __cplusplus

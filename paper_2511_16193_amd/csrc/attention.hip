@@ -390,7 +390,8 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         // up to four 16-row tiles per work-group; more stacked rows are split over row groups
         AttnArgs b = a;
         const int tiles = rp / 16;
-        b.row_groups = (tiles + 3) / 4;
+        const int cap = std::min(4, std::max(1, a.max_row_tiles));
+        b.row_groups = (tiles + cap - 1) / cap;
         const int R = b.row_groups == 1 ? std::max(tiles, a.min_row_tiles) : (tiles + b.row_groups - 1) / b.row_groups;
         dim3 grid((a.n_work * a.Hkv + 7) / 8 * 8 * b.row_groups);
         auto launch = [&](auto kern, int r) -> hipError_t {

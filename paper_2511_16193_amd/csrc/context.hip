@@ -185,6 +185,7 @@ struct sv_ctx {
     bool packed;                                          // projection weights are in fragment order
     bool attn_generic;
     int attn_min_rt;
+    int attn_max_rt;
     int attn_chunk;                                       // keys per split-KV chunk of the staged batch
     int attn_chunk_opt;                                   // 0 = chosen per batch, else fixed by option
     unsigned prof_mask;                                   // kinds of kernels to time with events
@@ -314,6 +315,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->packed = w->packed != 0;
     c->attn_generic = false;
     c->attn_min_rt = 1;
+    c->attn_max_rt = 3;            // four tiles leave the kernel short of registers (it spills)
     c->attn_chunk = kChunkKeys;
     c->attn_chunk_opt = 0;
     c->prof_mask = 0;
@@ -606,7 +608,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
         aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work; aa.req_chunk = c->at<int32_t>(L.req_chunk);
         aa.out_packed = c->packed;
-        aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
+        aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
         aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
         {
             ProfScope prof(c, SV_PROF_ATTENTION);
@@ -838,7 +840,7 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
     aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(c->lay.work); aa.n_work = c->n_work; aa.req_chunk = c->at<int32_t>(c->lay.req_chunk);
     aa.out_packed = false;
-    aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt;
+    aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
     SV_HIP(c, attention(aa, c->stream));
     return SV_OK;
@@ -906,6 +908,10 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
         case SV_OPT_ATTN_CHUNK_KEYS:
             if (value != 0 && (value < kChunkKeys || value % 128 != 0)) return c->fail(SV_EINVAL, "chunk of %d keys", value);
             c->attn_chunk_opt = value;
+            return SV_OK;
+        case SV_OPT_ATTN_MAX_ROW_TILES:
+            if (value < 1 || value > 4) return c->fail(SV_EINVAL, "row tiles %d", value);
+            c->attn_max_rt = value;
             return SV_OK;
         case SV_OPT_ATTN_MIN_ROW_TILES:
             if (value < 1 || value > 4) return c->fail(SV_EINVAL, "row tiles %d", value);
