@@ -87,8 +87,11 @@ def test_attention_bf16_matches_oracle(k, n_chains, group):
     for b in range(B):
         ver.kv_write(b, 0, 0, ks[b].to(DEV), vs[b].to(DEV))
     _, _, vis = OV.new_token_layout(k, n_chains)
-    for generic in (0, 1):
+    # the MFMA kernel with at most 3 (default), 4, 2 and 1 row tiles per work-group (more stacked rows go to row
+    # groups), then the generic kernel
+    for generic, max_tiles in ((0, 3), (0, 4), (0, 2), (0, 1), (1, 3)):
         ver.set_option(P.SV_OPT_ATTN_GENERIC, generic)
+        ver.set_option(P.SV_OPT_ATTN_MAX_ROW_TILES, max_tiles)
         got = ver.op_attention(ids, n, k, 0, q.to(DEV))
         torch.cuda.synchronize()
         got = got.float().cpu().numpy().reshape(B, n, hq, hd)
@@ -98,7 +101,7 @@ def test_attention_bf16_matches_oracle(k, n_chains, group):
             spread = M.attend(q[b * n:(b + 1) * n].double().numpy(), ks[b].double().numpy(),
                               np.abs(vs[b].double().numpy()), mask)
             tol = 2.0 ** -8 * (np.abs(want) + spread) + 1e-6
-            assert np.all(np.abs(got[b] - want) <= tol), (generic, b, L, float(np.max(np.abs(got[b] - want))))
+            assert np.all(np.abs(got[b] - want) <= tol), (generic, max_tiles, b, L, float(np.max(np.abs(got[b] - want))))
     ver.close()
 
 
