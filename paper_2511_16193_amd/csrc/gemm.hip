@@ -291,10 +291,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(
 // reads, PD k-slices ahead, with no LDS and no barrier on that path.  Only the activations, which every
 // wave needs, go through LDS: KA 16-wide slices of all MT 32-token tiles per fill (packed order too, so
 // a fill is a handful of contiguous 1 KB copies), double buffered, one barrier per fill.
-template <int MT, int NT, int KA, int PD, bool GLU = false>
-__global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_ws_kernel(
+template <int MT, int NT, int KA, int PD, bool GLU>
+__device__ __forceinline__ void gemm_bf16_ws_body(
     const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
-    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n, int tn0) {
+    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n, int tn0, int block_id) {
     constexpr int BM = 32 * MT, BN = 128 * NT;
     constexpr int AFR = MT * KA;                          // activation fragments per fill
     static_assert(AFR % 4 == 0, "fill must split over 4 waves");
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_w
     __shared__ __attribute__((aligned(16))) unsigned char abuf[2][AFR * 1024];
 
     const int nblk = tiles_m * tiles_n * splits;
-    int logical = xcd_remap(blockIdx.x, nblk);
+    int logical = xcd_remap(block_id, nblk);
     const int tm = logical % tiles_m;
     logical /= tiles_m;
     const int sp = logical % splits;
@@ -496,6 +496,26 @@ __global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_w
     }
 }
 
+template <int MT, int NT, int KA, int PD, bool GLU = false>
+__global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_ws_kernel(
+    const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
+    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n, int tn0) {
+    gemm_bf16_ws_body<MT, NT, KA, PD, GLU>(Ap, Wp, out, M, N, K, k_per_split, splits, tiles_m, tiles_n, tn0, blockIdx.x);
+}
+
+// Gate/up projection with a short last round: the first n_main work-groups are 160-row ones over the strips
+// [0, strips_main); the rest are 32-row ones over the remaining strips.  One launch: the small work-groups
+// start on whichever CUs free up first instead of waiting for the whole main round.
+__global__ __launch_bounds__(256, 1) void gemm_bf16_ws_glu_mixed_kernel(
+    const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out, int M, int N, int K,
+    int tiles_m, int strips_main, int tiles_m1, int strips_tail) {
+    const int n_main = tiles_m * strips_main;
+    if ((int)blockIdx.x < n_main)
+        gemm_bf16_ws_body<5, 2, 8, 8, true>(Ap, Wp, out, M, N, K, K, 1, tiles_m, strips_main, 0, blockIdx.x);
+    else
+        gemm_bf16_ws_body<1, 2, 8, 8, true>(Ap, Wp, out, M, N, K, K, 1, tiles_m1, strips_tail, strips_main, blockIdx.x - n_main);
+}
+
 // Activations [M, K] row-major -> packed [ceil(M/32)][K/16][64 lanes][8]: lane 32*g + r of a fragment holds
 // row 32*tile + r, elements 8*g .. 8*g+7 of the slice; rows beyond M are written as zeros.
 __global__ void pack_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int M, int K) {
@@ -535,19 +555,22 @@ hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out,
     if (F % 128 == 0 && K % 128 == 0) {
         // 128-feature strips, gate and up in one wave.  One work-group per CU: the launch runs in rounds of 256,
         // and a last round that is less than half full would leave most CUs idle for a whole work-group's time.
-        // Its strips are then given to a second launch of 32-row work-groups (five times as many, a fifth as long).
+        // Its strips are then given to 32-row work-groups (five times as many, a fifth as long) at the end of the
+        // same launch.
         const int tiles_m = (M + 159) / 160, strips = F / 128;
         const int rem = (strips * tiles_m) % 256;
         const int strips_tail = rem > 0 && rem <= 128 ? (rem + tiles_m - 1) / tiles_m : 0;
         const int strips_main = strips - strips_tail;
-        if (strips_main > 0)
+        const int tiles_m1 = (M + 31) / 32;
+        if (strips_tail == 0)
             hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 2, 8, 8, true>), dim3(tiles_m * strips_main), dim3(256), 0, st, Ap, Wp,
                                out, M, 2 * F, K, K, 1, tiles_m, strips_main, 0);
-        if (strips_tail > 0) {
-            const int tiles_m1 = (M + 31) / 32;
+        else if (strips_main == 0)
             hipLaunchKernelGGL((gemm_bf16_ws_kernel<1, 2, 8, 8, true>), dim3(tiles_m1 * strips_tail), dim3(256), 0, st, Ap, Wp,
-                               out, M, 2 * F, K, K, 1, tiles_m1, strips_tail, strips_main);
-        }
+                               out, M, 2 * F, K, K, 1, tiles_m1, strips_tail, 0);
+        else
+            hipLaunchKernelGGL(gemm_bf16_ws_glu_mixed_kernel, dim3(tiles_m * strips_main + tiles_m1 * strips_tail), dim3(256), 0,
+                               st, Ap, Wp, out, M, 2 * F, K, tiles_m, strips_main, tiles_m1, strips_tail);
         return hipGetLastError();
     }
     const int tiles_m = (M + 159) / 160, tiles_n = F / 64;
