@@ -47,20 +47,24 @@ int pick_splits(int M, int N, int K) {
 // at 3.5 TB/s (written here, read again by the consumer).
 struct WsPlan { int splits; bool wide; };
 WsPlan plan_ws(int M, int N, int K, bool allow_split) {
-    const int tiles_m = (M + 159) / 160, slices = K / 16;
+    const int mt = gemm_bf16_ws_row_tiles(M);                 // 32-row tiles per work-group (1..5)
+    const int tiles_m = (M + 32 * mt - 1) / (32 * mt), slices = K / 16;
+    const double rows = mt / 5.0;                             // the constants above are for five tiles
     WsPlan best{1, false};
     double best_t = 1e30;
     for (int wide = 0; wide < 2; ++wide) {
         if (wide && N % 256 != 0) continue;
-        const double iso = wide ? 0.2 : 0.125, rate = wide ? 0.9e9 : 0.78e9;      // flop per microsecond
-        const double work = 2.0 * 160 * (wide ? 256 : 128) * 16;                  // flop per work-group slice
-        const int cap = wide ? 256 : 512;
+        const double iso = std::max(0.05, (wide ? 0.2 : 0.125) * rows), rate = wide ? 0.9e9 : 0.78e9;   // flop per microsecond
+        const double work = 2.0 * 32 * mt * (wide ? 256 : 128) * 16;                                    // flop per work-group slice
+        const int cap = wide && mt == 5 ? 256 : 512;
         auto slice_time = [&](int n) { return std::max(iso, n * work / rate); };
         for (int s = 1; s <= (allow_split ? kMaxSplitsWs : 1); ++s) {
             if (slices % (4 * s) != 0) continue;
             const int blocks = (N / (wide ? 256 : 128)) * tiles_m * s;
             const int full = blocks / cap, rem = blocks % cap;
             double t = (double)full * (slices / s) * slice_time(cap) + (rem ? (slices / s) * slice_time(rem) : 0.0);
+            // a weight stream cannot beat the memory system whatever the products cost
+            t = std::max(t, (double)N * K * 2.0 / 5.0e6);
             if (s > 1) t += (double)s * M * N * 4.0 / 3.5e6;
             if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0}; }
         }
@@ -117,10 +121,10 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
             part = std::max(part, (size_t)(m.dtype == SV_BF16 ? pick_splits(M, sh[0], sh[1]) : 1) * M * sh[0]);
     }
     if (m.dtype == SV_BF16)                                 // the same for the plans of the weight-streaming kernel
-        for (int tm = 1; tm <= (T + 159) / 160; ++tm) {
-            const int M = std::min(tm * 160, T);
+        for (int M = 32; M < T + 32; M += 32) {            // the plan depends on the 32-row tile count only
+            const int Mc = std::min(M, T);
             for (auto& sh : shapes)
-                if (sh[1] % 64 == 0) part = std::max(part, (size_t)plan_ws(M, sh[0], sh[1], true).splits * M * sh[0]);
+                if (sh[1] % 64 == 0) part = std::max(part, (size_t)plan_ws(Mc, sh[0], sh[1], true).splits * Mc * sh[0]);
         }
     L.part = take(sizeof(float) * part);
     L.act = take(es * Tp * F);

@@ -557,15 +557,24 @@ hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out,
         // and a last round that is less than half full would leave most CUs idle for a whole work-group's time.
         // Its strips are then given to 32-row work-groups (five times as many, a fifth as long) at the end of the
         // same launch.
-        const int tiles_m = (M + 159) / 160, strips = F / 128;
+        const int mt = gemm_bf16_ws_row_tiles(M);
+        const int tiles_m = (M + 32 * mt - 1) / (32 * mt), strips = F / 128;
         const int rem = (strips * tiles_m) % 256;
-        const int strips_tail = rem > 0 && rem <= 128 ? (rem + tiles_m - 1) / tiles_m : 0;
+        const int strips_tail = mt == 5 && rem > 0 && rem <= 128 ? (rem + tiles_m - 1) / tiles_m : 0;
         const int strips_main = strips - strips_tail;
         const int tiles_m1 = (M + 31) / 32;
-        if (strips_tail == 0)
-            hipLaunchKernelGGL((gemm_bf16_ws_kernel<5, 2, 8, 8, true>), dim3(tiles_m * strips_main), dim3(256), 0, st, Ap, Wp,
-                               out, M, 2 * F, K, K, 1, tiles_m, strips_main, 0);
-        else if (strips_main == 0)
+        auto launch = [&](auto kern) {
+            hipLaunchKernelGGL(kern, dim3(tiles_m * strips), dim3(256), 0, st, Ap, Wp, out, M, 2 * F, K, K, 1, tiles_m, strips, 0);
+        };
+        if (strips_tail == 0) {
+            switch (mt) {
+                case 1: launch(gemm_bf16_ws_kernel<1, 2, 8, 8, true>); break;
+                case 2: launch(gemm_bf16_ws_kernel<2, 2, 8, 8, true>); break;
+                case 3: launch(gemm_bf16_ws_kernel<3, 2, 8, 8, true>); break;
+                case 4: launch(gemm_bf16_ws_kernel<4, 2, 8, 8, true>); break;
+                default: launch(gemm_bf16_ws_kernel<5, 2, 8, 8, true>); break;
+            }
+        } else if (strips_main == 0)
             hipLaunchKernelGGL((gemm_bf16_ws_kernel<1, 2, 8, 8, true>), dim3(tiles_m1 * strips_tail), dim3(256), 0, st, Ap, Wp,
                                out, M, 2 * F, K, K, 1, tiles_m1, strips_tail, 0);
         else
@@ -584,13 +593,30 @@ hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out,
 }
 
 // Weight-streaming projection: packed activations, packed weights.  wide: 256 features per work-group.
+// 32-row tiles per work-group for M rows: as few work-groups along the rows as five tiles each allow, then no
+// more tiles each than those work-groups need (320 rows: 2 x 5; 512 rows: 4 x 4; 64 rows: 1 x 2).
+int gemm_bf16_ws_row_tiles(int M) {
+    const int tiles = (M + 31) / 32, groups = (tiles + 4) / 5;
+    return (tiles + groups - 1) / groups;
+}
+
 hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool wide,
                         hipStream_t st) {
     const bool long_fill = (K / splits) % 128 == 0;
-    if (wide) return long_fill ? launch_ws<5, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st)
-                               : launch_ws<5, 2, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
-    return long_fill ? launch_ws<5, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st)
-                     : launch_ws<5, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
+    if (!long_fill)          // short reductions (small models): the five-tile form only
+        return wide ? launch_ws<5, 2, 4, 4>(Ap, Wp, out, M, N, K, splits, st) : launch_ws<5, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
+    switch (gemm_bf16_ws_row_tiles(M) * 2 + (wide ? 1 : 0)) {
+        case 2: return launch_ws<1, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 3: return launch_ws<1, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 4: return launch_ws<2, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 5: return launch_ws<2, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 6: return launch_ws<3, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 7: return launch_ws<3, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 8: return launch_ws<4, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 9: return launch_ws<4, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        case 10: return launch_ws<5, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+        default: return launch_ws<5, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
+    }
 }
 
 // fp32 path (small models only): 32x32 output tile per 256-thread group, 4 outputs per thread, every

@@ -15,6 +15,7 @@ hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t
 hipError_t pack_rows(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st);
 hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool wide,
                         hipStream_t st);
+int gemm_bf16_ws_row_tiles(int M);
 hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st);
 hipError_t gemm_f32(const float* A, const float* W, float* out, int M, int N, int K, hipStream_t st);
 
