@@ -121,11 +121,9 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
             part = std::max(part, (size_t)(m.dtype == SV_BF16 ? pick_splits(M, sh[0], sh[1]) : 1) * M * sh[0]);
     }
     if (m.dtype == SV_BF16)                                 // the same for the plans of the weight-streaming kernel
-        for (int M = 32; M < T + 32; M += 32) {            // the plan depends on the 32-row tile count only
-            const int Mc = std::min(M, T);
+        for (int M = 1; M <= T; ++M)                       // every row count a call can bring (the plan weighs M itself)
             for (auto& sh : shapes)
-                if (sh[1] % 64 == 0) part = std::max(part, (size_t)plan_ws(Mc, sh[0], sh[1], true).splits * Mc * sh[0]);
-        }
+                if (sh[1] % 64 == 0) part = std::max(part, (size_t)plan_ws(M, sh[0], sh[1], true).splits * M * sh[0]);
     L.part = take(sizeof(float) * part);
     L.act = take(es * Tp * F);
     L.logits = take(sizeof(float) * (size_t)T * m.vocab);
