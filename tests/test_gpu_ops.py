@@ -42,10 +42,12 @@ def test_gemm_bf16_matches_float64_product(variant, M_, N, K, splits):
 @pytest.mark.parametrize("M_,N,K,splits,wide", [(320, 512, 1024, 1, True), (37, 256, 512, 4, True), (129, 128, 64, 1, False),
                                                (1, 384, 2048, 8, False), (700, 640, 448, 1, False),
                                                (321, 768, 3584, 2, True), (320, 1024, 192, 1, True),
-                                               (64, 256, 2368, 1, True)])
+                                               (64, 256, 2368, 1, True), (96, 256, 512, 2, True), (180, 384, 1024, 1, False),
+                                               (513, 256, 256, 1, True)])
 def test_gemm_weight_streaming_matches_float64_product(M_, N, K, splits, wide):
     """The weight-streaming kernel on packed operands: ragged row tiles (rows beyond M read as the last
-    tile), both strip widths, fills of 8 and of 4 k-slices, every split count."""
+    tile), both strip widths, fills of 8 and of 4 k-slices, every split count, every number of 32-row tiles per
+    work-group (1 to 5; 513 rows: four groups of five tiles with 127 padding rows)."""
     from paper_2511_16193_amd import op_gemm_bf16_ws, op_pack_weight, op_pack_rows
     a = bf16_cpu((M_, K), 1.0, 1)
     w = bf16_cpu((N, K), 0.02, 2)
