@@ -110,6 +110,7 @@ def main():
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--cpu-seqs", type=int, default=16, help="requests in the oracle sample (0 = skip)")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--no-graph", action="store_true", help="skip the extra pass that replays the steps from a HIP graph")
     ap.add_argument("--attn-chunk", type=int, default=None, help="keys per split-KV chunk (tuning)")
     ap.add_argument("--attn-max-row-tiles", type=int, default=None, help="16-row tiles per attention work-group (tuning)")
     ap.add_argument("--drafts", choices=["noisy-target", "independent"], default="noisy-target",
@@ -133,6 +134,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(1)
+    # a stream of its own for everything: the library can only capture its launches into a graph off the null stream
+    torch.cuda.set_stream(torch.cuda.Stream())
     shape = W.CONFIGS[args.config]
     if args.batch is not None:
         shape = W.scaled_down(shape, batch=args.batch)
@@ -169,6 +172,20 @@ def main():
     run(args.steps)
     torch.cuda.synchronize()
     plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the same steps replayed from a HIP graph (reported beside the contract's figure: the event brackets of the
+    # timed region below cannot be recorded inside a graph)
+    graph_ms = None
+    if not args.no_graph:
+        case.ver.set_option(P.SV_OPT_GRAPH, 1)
+        run(3)                                     # plain launches, capture, first replay
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        case.ver.set_option(P.SV_OPT_GRAPH, 0)
+        log(f"graph replay: {graph_ms:.3f} ms per step")
 
     # pre-pass (not timed): every kernel kind bracketed by events, to find the kind that takes most of the step
     # and to time the others
@@ -256,6 +273,7 @@ def main():
         "accepted_drafts_tokens_per_s": int(acc.sum()) / (ms_per_step * 1e-3),
         "roofline": dominant, "roofline_other": other,
         "sampler_ms_per_step": samp_ms, "ms_per_step_without_event_brackets": plain_ms,
+        "ms_per_step_graph_replay": graph_ms,
         "cpu_baseline": cpu,
     }
     case.close()

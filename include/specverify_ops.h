@@ -93,10 +93,13 @@ int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launch
  *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for
  *   SV_OPT_ATTN_MAX_ROW_TILES  most 16-row tiles (1..4, default 3) one work-group of the bf16 attention takes;
  *                           more stacked rows are split over row groups that stream the same keys
+ *   SV_OPT_GRAPH  1 = verify_step replays its device work from a HIP graph captured on the second step with the
+ *                 same batch shape and the same caller buffers (the first runs as plain launches); needs a context
+ *                 stream other than the null stream; not used while sv_profile_enable brackets are on.  Default 0
  *   SV_OPT_ATTN_CHUNK_KEYS  keys per split-KV chunk of the bf16 attention (multiple of 128, at least 1024; 0 = chosen per
  *                           batch from the lengths, default) */
 enum { SV_OPT_GEMM_VARIANT = 1, SV_OPT_ATTN_GENERIC = 2, SV_OPT_ATTN_MIN_ROW_TILES = 3, SV_OPT_ATTN_CHUNK_KEYS = 4,
-       SV_OPT_ATTN_MAX_ROW_TILES = 5 };
+       SV_OPT_ATTN_MAX_ROW_TILES = 5, SV_OPT_GRAPH = 6 };
 int sv_set_option(sv_ctx *, int option, int value);
 
 #ifdef __cplusplus

@@ -37,7 +37,8 @@ __global__ __launch_bounds__(256, R == 1 ? 2 : 1) void attn_bf16_kernel(AttnArgs
     // and started together: the second reader of a tile finds it in that XCD's L2.
     const int slot = blockIdx.x / (8 * a.row_groups), rem = blockIdx.x % (8 * a.row_groups);
     const int rg = rem >> 3, pair = slot * 8 + (rem & 7);
-    if (pair >= a.n_work * a.Hkv) return;
+    const int n_items = a.n_work_dev ? *a.n_work_dev : a.n_work;
+    if (pair >= n_items * a.Hkv) return;
     const int hkv = pair % a.Hkv;
     const int4 item = reinterpret_cast<const int4*>(a.work)[pair / a.Hkv];
     const int b = item.x >> 16, chunk = item.x & 0xffff;
@@ -393,7 +394,8 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         const int cap = std::min(4, std::max(1, a.max_row_tiles));
         b.row_groups = (tiles + cap - 1) / cap;
         const int R = b.row_groups == 1 ? std::max(tiles, a.min_row_tiles) : (tiles + b.row_groups - 1) / b.row_groups;
-        dim3 grid((a.n_work * a.Hkv + 7) / 8 * 8 * b.row_groups);
+        const int items = a.grid_items > 0 ? a.grid_items : a.n_work;
+        dim3 grid((items * a.Hkv + 7) / 8 * 8 * b.row_groups);
         auto launch = [&](auto kern, int r) -> hipError_t {
             const size_t lds = (size_t)4 * HD * (16 * r + 1) * sizeof(float);
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -97,7 +97,7 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.upd = take(sizeof(int32_t) * 3 * (size_t)r.max_batch * 8);
     L.max_chunks = (int)(((size_t)r.max_pages_per_seq * r.page_size + kChunkKeys - 1) / kChunkKeys);
     L.work = take(sizeof(int32_t) * 4 * (size_t)r.max_batch * L.max_chunks);
-    L.req_chunk = take(sizeof(int32_t) * 2 * (size_t)r.max_batch);
+    L.req_chunk = take(sizeof(int32_t) * (2 * (size_t)r.max_batch + 1));      // + the number of work items
     L.row_tok = take(sizeof(int32_t) * T);
     L.row_pos = take(sizeof(int32_t) * T);
     L.row_slot = take(sizeof(int32_t) * T);
@@ -188,6 +188,16 @@ struct sv_ctx {
     bool attn_generic;
     int attn_min_rt;
     int attn_max_rt;
+    bool use_graph;                                       // replay verify_step's device work from captured graphs
+    bool graph_launch_shape;                              // launches take shapes that do not depend on the lengths
+    struct GraphEntry {
+        int B, k, N;
+        const void* ptr[9];
+        hipGraphExec_t exec;
+        unsigned long long used;
+    };
+    std::vector<GraphEntry> graphs;
+    unsigned long long graph_clock;
     int attn_chunk;                                       // keys per split-KV chunk of the staged batch
     int attn_chunk_opt;                                   // 0 = chosen per batch, else fixed by option
     unsigned prof_mask;                                   // kinds of kernels to time with events
@@ -317,11 +327,14 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->packed = w->packed != 0;
     c->attn_generic = false;
     c->attn_min_rt = 1;
+    c->use_graph = false;
+    c->graph_launch_shape = false;
+    c->graph_clock = 0;
     c->attn_max_rt = 3;            // four tiles leave the kernel short of registers (it spills)
     c->attn_chunk = kChunkKeys;
     c->attn_chunk_opt = 0;
     c->prof_mask = 0;
-    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8 + 4 * L.max_chunks + 2) + 8;
+    const size_t slot_ints = (size_t)r->max_batch * (1 + 3 * 8 + 4 * L.max_chunks + 2) + 16;
     for (int i = 0; i < kRing; ++i) { c->staging[i] = nullptr; c->staged[i] = nullptr; c->staged_valid[i] = false; }
     for (int i = 0; i < kRing; ++i) {
         if (hipHostMalloc(reinterpret_cast<void**>(&c->staging[i]), slot_ints * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
@@ -341,9 +354,12 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     return SV_OK;
 }
 
+static void drop_graphs(sv_ctx* c);
+
 extern "C" void verify_destroy(sv_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
+    drop_graphs(c);
     for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
     for (int i = 0; i < kRing; ++i) {
@@ -514,7 +530,7 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
         // page table; the live length is read beside it and only clips the end).  Pieces are cut from the
         // upper bounds of the lengths: equal parts, whole 32-key tiles.
         int32_t* req = upd + 3 * nupd;                   // per request: keys per piece, pieces
-        int32_t* work = req + 2 * B;
+        int32_t* work = req + 2 * c->rt.max_batch + 1;
         struct Item { int len, b, ch, seq, kbeg, kend; };
         std::vector<Item> items;
         for (int b = 0; b < B; ++b) {
@@ -531,7 +547,8 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
             work[4 * nw] = (t.b << 16) | t.ch; work[4 * nw + 1] = t.seq; work[4 * nw + 2] = t.kbeg; work[4 * nw + 3] = t.kend;
             ++nw;
         }
-        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.req_chunk), req, 2 * B * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+        req[2 * c->rt.max_batch] = nw;                    // read by launches that were captured into a graph
+        SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.req_chunk), req, (2 * c->rt.max_batch + 1) * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
         SV_HIP(c, hipMemcpyAsync(c->at<int32_t>(c->lay.work), work, 4 * nw * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
         c->n_work = nw;
     }
@@ -612,6 +629,12 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         aa.out_packed = c->packed;
         aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
         aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
+        aa.n_work_dev = nullptr; aa.grid_items = 0;
+        if (c->graph_launch_shape) {      // nothing in the launch may depend on the lengths
+            aa.max_chunks = L.max_chunks;
+            aa.n_work_dev = c->at<int32_t>(L.req_chunk) + 2 * c->rt.max_batch;
+            aa.grid_items = B * L.max_chunks;
+        }
         {
             ProfScope prof(c, SV_PROF_ATTENTION);
             SV_HIP(c, attention(aa, st));
@@ -674,19 +697,11 @@ extern "C" int verify_prefill(sv_ctx* c, int32_t id, const int32_t* tokens, int3
     return SV_OK;
 }
 
-extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts, const float* draft_probs,
-                           const float* uniforms, const sv_out* out) {
-    if (!c || !bt || !out) return SV_EINVAL;
-    const int B = bt->B, k = bt->k, N = bt->N;
-    if (B <= 0 || B > c->rt.max_batch || k < 0 || k > c->rt.max_k || N <= 0 || N > c->rt.max_chains)
-        return c->fail(SV_EINVAL, "batch %d / k %d / chains %d outside the limits given at init", B, k, N);
-    if (!bt->seq_ids || !bt->last_tokens || (k > 0 && !drafts) || !out->accepted_len || !out->out_tokens || !out->best_chain)
-        return c->fail(SV_EINVAL, "null argument");
-    if (c->rt.verify_mode == SV_STOCHASTIC && !uniforms) return c->fail(SV_EINVAL, "stochastic verification needs uniforms");
-    const int n = 1 + N * k;
-    SV_TRY(stage_batch(c, bt->seq_ids, B, n));
-    int max_ub = 0;
-    for (int b = 0; b < B; ++b) max_ub = std::max(max_ub, c->seqs[bt->seq_ids[b]].len_ub);
+// Everything verify_step enqueues after the batch is staged: forward pass, accept/reject + draw, chain choice,
+// rollback, optional copy of the logits.
+static int step_device_work(sv_ctx* c, const sv_batch* bt, const int32_t* drafts, const float* draft_probs,
+                            const float* uniforms, const sv_out* out, int max_ub) {
+    const int B = bt->B, k = bt->k, N = bt->N, n = 1 + N * k;
     SV_TRY(forward_rows(c, B, n, k, bt->last_tokens, drafts, max_ub));
 
     const Layout& L = c->lay;
@@ -714,6 +729,81 @@ extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts,
     if (out->logits)
         SV_HIP(c, hipMemcpyAsync(out->logits, sa.logits, sizeof(float) * (size_t)B * n * c->model.vocab,
                                  hipMemcpyDeviceToDevice, c->stream));
+    return SV_OK;
+}
+
+static void drop_graphs(sv_ctx* c) {
+    for (auto& g : c->graphs)
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    c->graphs.clear();
+}
+
+// Graph replay of the step's device work.  A step's launches depend on the batch shape and on the caller's
+// buffers only (the lengths reach the kernels through device memory; the attention grid is sized for the most
+// work items the shape can have), so one captured graph serves every step with the same shape and buffers.
+// The first step of a kind runs as plain launches (one-off set-up calls are not capturable), the second is
+// captured, later ones replay.  Returns 1 if the work was enqueued through a graph, 0 if the caller should
+// enqueue it itself, < 0 on error.
+static int step_through_graph(sv_ctx* c, const sv_batch* bt, const int32_t* drafts, const float* draft_probs,
+                              const float* uniforms, const sv_out* out, int max_ub) {
+    if (!c->use_graph || c->stream == nullptr || c->prof_mask != 0) return 0;
+    const void* ptr[9] = {bt->last_tokens, drafts, draft_probs, uniforms, bt->draft_lens,
+                          out->accepted_len, out->out_tokens, out->best_chain, out->logits};
+    sv_ctx::GraphEntry* e = nullptr;
+    for (auto& g : c->graphs)
+        if (g.B == bt->B && g.k == bt->k && g.N == bt->N && memcmp(g.ptr, ptr, sizeof(ptr)) == 0) e = &g;
+    if (!e) {
+        if (c->graphs.size() >= 8) {                       // forget the least recently used
+            size_t old = 0;
+            for (size_t i = 1; i < c->graphs.size(); ++i)
+                if (c->graphs[i].used < c->graphs[old].used) old = i;
+            if (c->graphs[old].exec) (void)hipGraphExecDestroy(c->graphs[old].exec);
+            c->graphs.erase(c->graphs.begin() + old);
+        }
+        sv_ctx::GraphEntry g;
+        g.B = bt->B; g.k = bt->k; g.N = bt->N;
+        memcpy(g.ptr, ptr, sizeof(ptr));
+        g.exec = nullptr;
+        g.used = ++c->graph_clock;
+        c->graphs.push_back(g);
+        return 0;                                           // first step of this kind: plain launches
+    }
+    e->used = ++c->graph_clock;
+    if (!e->exec) {
+        hipGraph_t graph = nullptr;
+        SV_HIP(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+        c->graph_launch_shape = true;
+        const int rc = step_device_work(c, bt, drafts, draft_probs, uniforms, out, max_ub);
+        c->graph_launch_shape = false;
+        const hipError_t ec = hipStreamEndCapture(c->stream, &graph);
+        if (rc != SV_OK || ec != hipSuccess || !graph) {
+            if (graph) (void)hipGraphDestroy(graph);
+            return rc != SV_OK ? rc : c->fail(SV_EHIP, "stream capture failed: %s", hipGetErrorString(ec));
+        }
+        const hipError_t ei = hipGraphInstantiate(&e->exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (ei != hipSuccess) { e->exec = nullptr; return c->fail(SV_EHIP, "graph instantiation failed: %s", hipGetErrorString(ei)); }
+    }
+    SV_HIP(c, hipGraphLaunch(e->exec, c->stream));
+    return 1;
+}
+
+extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts, const float* draft_probs,
+                           const float* uniforms, const sv_out* out) {
+    if (!c || !bt || !out) return SV_EINVAL;
+    const int B = bt->B, k = bt->k, N = bt->N;
+    if (B <= 0 || B > c->rt.max_batch || k < 0 || k > c->rt.max_k || N <= 0 || N > c->rt.max_chains)
+        return c->fail(SV_EINVAL, "batch %d / k %d / chains %d outside the limits given at init", B, k, N);
+    if (!bt->seq_ids || !bt->last_tokens || (k > 0 && !drafts) || !out->accepted_len || !out->out_tokens || !out->best_chain)
+        return c->fail(SV_EINVAL, "null argument");
+    if (c->rt.verify_mode == SV_STOCHASTIC && !uniforms) return c->fail(SV_EINVAL, "stochastic verification needs uniforms");
+    const int n = 1 + N * k;
+    SV_TRY(stage_batch(c, bt->seq_ids, B, n));
+    int max_ub = 0;
+    for (int b = 0; b < B; ++b) max_ub = std::max(max_ub, c->seqs[bt->seq_ids[b]].len_ub);
+    const int via_graph = step_through_graph(c, bt, drafts, draft_probs, uniforms, out, max_ub);
+    if (via_graph < 0) return via_graph;
+    if (via_graph == 0) SV_TRY(step_device_work(c, bt, drafts, draft_probs, uniforms, out, max_ub));
     for (int b = 0; b < B; ++b) c->seqs[bt->seq_ids[b]].len_ub += k + 1;
     return SV_OK;
 }
@@ -844,6 +934,7 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.out_packed = false;
     aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
+    aa.n_work_dev = nullptr; aa.grid_items = 0;
     SV_HIP(c, attention(aa, c->stream));
     return SV_OK;
 }
@@ -898,6 +989,7 @@ extern "C" int sv_seq_set_lens(sv_ctx* c, const int32_t* seq_ids, const int32_t*
 
 extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
     if (!c) return SV_EINVAL;
+    drop_graphs(c);                                       // captured launches carry the options they were made with
     switch (option) {
         case SV_OPT_GEMM_VARIANT:
             if (value < -1 || value > 6)
@@ -910,6 +1002,11 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
         case SV_OPT_ATTN_CHUNK_KEYS:
             if (value != 0 && (value < kChunkKeys || value % 128 != 0)) return c->fail(SV_EINVAL, "chunk of %d keys", value);
             c->attn_chunk_opt = value;
+            return SV_OK;
+        case SV_OPT_GRAPH:
+            if (value != 0 && c->stream == nullptr) return c->fail(SV_EINVAL, "graph replay needs a stream of its own, not the null stream");
+            c->use_graph = value != 0;
+            drop_graphs(c);
             return SV_OK;
         case SV_OPT_ATTN_MAX_ROW_TILES:
             if (value < 1 || value > 4) return c->fail(SV_EINVAL, "row tiles %d", value);

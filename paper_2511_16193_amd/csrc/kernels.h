@@ -70,6 +70,8 @@ struct AttnArgs {
     int chunk_keys, max_chunks;
     const int32_t* work; int n_work;    // items of the bf16 kernel, 4 ints each: request << 16 | chunk, sequence id, first key, end
     const int32_t* req_chunk;           // [B][2] keys per piece, pieces (from the host's upper bounds of the lengths)
+    const int32_t* n_work_dev;          // when set: the item count lives here (a captured launch cannot carry it)
+    int grid_items;                     // when > 0: items the grid is sized for (an upper bound of the item count)
     int min_row_tiles;                  // lower bound on the 16-row tiles of the bf16 kernel (tuning)
     int max_row_tiles;                  // most 16-row tiles one work-group takes (1..4); more rows -> row groups
     bool out_packed;                    // write `out` in the packed activation order (see act_index)
