@@ -123,7 +123,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the verification step on ONE GPU (requests shard across workers "
-              "with no exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "with no exchange between them); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
