@@ -607,9 +607,16 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
     SV_HIP(c, prep_rows(rp, st));
     SV_HIP(c, embed_rows(c->embed, m.dtype, rp.row_tok, h, T, d, st));
 
-    int pending = 0;      // split-K partials of the previous projection, still to be added to h
+    int pending = 0;      // split-K partials of the previous projection, still to be added to h;
+                          // -1: the expert outputs of the previous layer, still to be combined and added
+    auto norm = [&](const void* gain) -> hipError_t {
+        if (pending < 0)
+            return add_rmsnorm_experts(h, c->at<float>(L.moe_y), c->at<int32_t>(L.moe_inv), c->at<float>(L.moe_w), m.top_k, gain, a_norm,
+                                       T, d, m.rms_eps, c->packed, st);
+        return add_rmsnorm(h, part, pending, gain, a_norm, m.dtype, T, d, m.rms_eps, c->packed, st);
+    };
     for (int l = 0; l < m.n_layers; ++l) {
-        SV_HIP(c, add_rmsnorm(h, part, pending, c->ln1[l], a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
+        SV_HIP(c, norm(c->ln1[l]));
         int s_qkv = 1;
         SV_TRY(gemm(c, a_norm, c->wqkv[l], part, T, qkvw, d, &s_qkv));
         RopeAppend ra;
@@ -650,11 +657,11 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
             ma.top_ids = c->at<int32_t>(L.moe_ids); ma.top_w = c->at<float>(L.moe_w); ma.router_logits = c->at<float>(L.moe_logits);
             ma.cnt = c->at<int32_t>(L.moe_cnt); ma.tile_off = c->at<int32_t>(L.moe_off);
             ma.perm = c->at<int32_t>(L.moe_perm); ma.inv = c->at<int32_t>(L.moe_inv);
-            ma.act = c->at<bf16_t>(L.moe_act); ma.y = c->at<float>(L.moe_y); ma.out = part;
+            ma.act = c->at<bf16_t>(L.moe_act); ma.y = c->at<float>(L.moe_y); ma.out = nullptr;   // combined by the next norm
             ma.T = T; ma.d = d; ma.E = m.n_experts; ma.top_k = m.top_k; ma.F = m.d_expert;
             ProfScope prof(c, SV_PROF_MOE);
             SV_HIP(c, moe_ffn(ma, st));
-            pending = 1;
+            pending = -1;
             continue;
         }
         if (c->packed && m.d_ff % 64 == 0) {
@@ -668,7 +675,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
         }
         SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
     }
-    SV_HIP(c, add_rmsnorm(h, part, pending, c->final_norm, a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
+    SV_HIP(c, norm(c->final_norm));
     int one = 1;
     SV_TRY(gemm(c, a_norm, c->lm_head, c->at<float>(L.logits), T, m.vocab, d, &one, false));
     return SV_OK;

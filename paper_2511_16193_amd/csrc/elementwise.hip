@@ -38,10 +38,15 @@ __global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restr
 // One 256-thread group per row.  Each thread owns up to NV float4 pieces of the row; the loads of the
 // residual and of every split-K partial product are issued before the first use, so the row costs a
 // few memory round trips rather than one per element.
+// With `inv` set the addend is not S planes but the weighted sum of the row's top_k expert outputs
+// (part = expert outputs [padded row][d], row of assignment j at inv[t*top_k + j], weight wts[t*top_k + j]),
+// accumulated in slot order.
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int S,
                                                           int64_t part_stride, const T* __restrict__ w,
-                                                          T* __restrict__ a, int d, float eps, bool packed) {
+                                                          T* __restrict__ a, int d, float eps, bool packed,
+                                                          const int32_t* __restrict__ inv, const float* __restrict__ wts,
+                                                          int top_k) {
     __shared__ float red[4];
     const int t = blockIdx.x;
     const int nq = d >> 2;                               // float4 pieces per row
@@ -52,29 +57,60 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
         const int i = threadIdx.x + v * 256;
         x[v] = i < nq ? hr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    // partial planes four at a time: all their loads are in flight together, the additions keep plane order
-    for (int s0 = 0; s0 < S; s0 += 4) {
-        floatx4 y[4][NV];
+    if (inv) {
+        floatx4 acc[NV];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const floatx4* pr = reinterpret_cast<const floatx4*>(part + (s0 + u < S ? s0 + u : s0) * part_stride + (int64_t)t * d);
+        for (int v = 0; v < NV; ++v) acc[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int j0 = 0; j0 < top_k; j0 += 4) {             // four expert rows in flight at a time
+            floatx4 y[4][NV];
+            float wj[4];
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const int i = threadIdx.x + v * 256;
-                y[u][v] = (i < nq) & (s0 + u < S) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u < top_k ? j0 + u : j0;
+                wj[u] = j0 + u < top_k ? wts[(int64_t)t * top_k + j] : 0.f;
+                const floatx4* pr = reinterpret_cast<const floatx4*>(part + (int64_t)inv[(int64_t)t * top_k + j] * d);
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int i = threadIdx.x + v * 256;
+                    y[u][v] = (i < nq) & (j0 + u < top_k) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+                }
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j0 + u < top_k) {
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[v][e] = fmaf(wj[u], y[u][v][e], acc[v][e]);
+                }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int v = 0; v < NV; ++v) x[v] = x[v] + acc[v];
+    } else {
+    // partial planes four at a time: all their loads are in flight together, the additions keep plane order
+        for (int s0 = 0; s0 < S; s0 += 4) {
+            floatx4 y[4][NV];
 #pragma unroll
-            for (int v = 0; v < NV; ++v) x[v] = x[v] + y[u][v];
+            for (int u = 0; u < 4; ++u) {
+                const floatx4* pr = reinterpret_cast<const floatx4*>(part + (s0 + u < S ? s0 + u : s0) * part_stride + (int64_t)t * d);
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int i = threadIdx.x + v * 256;
+                    y[u][v] = (i < nq) & (s0 + u < S) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < NV; ++v) x[v] = x[v] + y[u][v];
+        }
     }
     float ss = 0.f;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
         const int i = threadIdx.x + v * 256;
         if (i < nq) {
-            if (S) hr[i] = x[v];
+            if (S | (inv != nullptr)) hr[i] = x[v];
             ss = fmaf(x[v][0], x[v][0], ss);
             ss = fmaf(x[v][1], x[v][1], ss);
             ss = fmaf(x[v][2], x[v][2], ss);
@@ -195,23 +231,28 @@ hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, floa
 
 template <typename T>
 static hipError_t add_rmsnorm_t(float* h, const float* part, int S, const T* w, T* a, int T_, int d, float eps, bool packed,
-                                hipStream_t st) {
+                                const int32_t* inv, const float* wts, int top_k, hipStream_t st) {
     const int64_t stride = (int64_t)T_ * d;
     const int nq = d / 4;
     if (d % 4 != 0 || nq > 256 * 8) return hipErrorInvalidValue;
     if (nq <= 256 * 2)
-        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 2>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 2>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed, inv, wts, top_k);
     else if (nq <= 256 * 4)
-        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 4>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 4>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed, inv, wts, top_k);
     else
-        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 8>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<T, 8>), dim3(T_), dim3(256), 0, st, h, part, S, stride, w, a, d, eps, packed, inv, wts, top_k);
     return hipGetLastError();
 }
 
 hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
                        bool packed, hipStream_t st) {
-    if (dtype == 1) return add_rmsnorm_t<bf16_t>(h, part, S, (const bf16_t*)w, (bf16_t*)a, T, d, eps, packed, st);
-    return add_rmsnorm_t<float>(h, part, S, (const float*)w, (float*)a, T, d, eps, packed, st);
+    if (dtype == 1) return add_rmsnorm_t<bf16_t>(h, part, S, (const bf16_t*)w, (bf16_t*)a, T, d, eps, packed, nullptr, nullptr, 0, st);
+    return add_rmsnorm_t<float>(h, part, S, (const float*)w, (float*)a, T, d, eps, packed, nullptr, nullptr, 0, st);
+}
+
+hipError_t add_rmsnorm_experts(float* h, const float* y, const int32_t* inv, const float* wts, int top_k, const void* w, void* a,
+                               int T, int d, float eps, bool packed, hipStream_t st) {
+    return add_rmsnorm_t<bf16_t>(h, y, 0, (const bf16_t*)w, (bf16_t*)a, T, d, eps, packed, inv, wts, top_k, st);
 }
 
 hipError_t rope_append(const RopeAppend& p, hipStream_t st) {

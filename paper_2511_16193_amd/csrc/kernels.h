@@ -37,6 +37,9 @@ hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, floa
 // h[t,:] += sum_s part[s][t,:] (S may be 0), then a[t,:] = storage(h * rsqrt(mean(h^2)+eps) * w)
 hipError_t add_rmsnorm(float* h, const float* part, int S, const void* w, void* a, int dtype, int T, int d, float eps,
                        bool packed, hipStream_t st);
+// the same with the addend = weighted sum of the row's top_k expert outputs y[inv[t*top_k + j]] (bf16 models)
+hipError_t add_rmsnorm_experts(float* h, const float* y, const int32_t* inv, const float* wts, int top_k, const void* w, void* a,
+                               int T, int d, float eps, bool packed, hipStream_t st);
 struct RopeAppend {
     const float* qkv_part; int S;       // [S][T][(Hq+2Hkv)*hd]
     const float* rope;                  // [T][hd/2][2]

@@ -405,7 +405,7 @@ hipError_t moe_ffn(const MoeArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(moe_group_kernel, dim3(1), dim3(1024), moe_group_lds_bytes(a.T, a.E), st, a);
     hipLaunchKernelGGL(moe_gemm_kernel<0>, dim3(a.E * (a.F / 64)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(moe_gemm_kernel<1>, dim3(a.E * (a.d / 128)), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(moe_combine_kernel, dim3(a.T), dim3(256), 0, st, a);
+    if (a.out) hipLaunchKernelGGL(moe_combine_kernel, dim3(a.T), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
