@@ -31,9 +31,12 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the copy-kernel calibration stated there), averaged over the launches of a kind in one step.
 MEASURED_TRAFFIC = {
-    # profiles/verify_step_cfg2_hbm_traffic.txt: projections (18514 MiB read + 2297 MiB written) / 113 launches;
+    # profiles/verify_step_cfg2_hbm_traffic.txt: projections (17994 MiB read + 2660 MiB written) / 113 launches;
     # attention main + merge kernel of one layer (602.5 MiB read + 11.6 MiB written)
-    "cfg2-7b-b64-k4": {"gemm": 193.1e6, "attention": 643.9e6},
+    "cfg2-7b-b64-k4": {"gemm": 191.7e6, "attention": 643.9e6},
+    # profiles/verify_step_cfg4_hbm_traffic.txt: expert FFN kernels of one layer (1404.9 MiB read + 77.1 MiB
+    # written); attention main + merge kernel of one layer (1227.1 MiB read + 20.2 MiB written)
+    "cfg4-moe-b128-k4": {"moe": 1554.0e6, "attention": 1307.9e6},
 }
 
 
