@@ -148,3 +148,29 @@ def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed)
     if k:
         assert accepted > 0
     case.close()
+
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_bf16_prefill_then_step(packed):
+    """Real prefill on both sides (no synthetic cache): prompts of 150 tokens run through verify_prefill in chunks,
+    every token cached; then one verification step on top.  Last-row logits of the prefill and the step's results
+    against the oracle."""
+    shape = W.scaled_down(SMALL_BF16, batch=3, k=4)
+    B, k, V = 3, 4, shape.vocab
+    case = Case(shape, [0] * B, verify_mode=OV.STOCHASTIC, synthetic_kv=False, extra_tokens=256, packed=packed)
+    prompts = W.make_tokens((B, 150), V, shape.seed, "prompt")
+    lo, ld = case.prefill(prompts)
+    assert np.max(np.abs(lo - ld)) < LOGIT_TOL["bf16"]
+    assert np.array_equal(case.device_lengths(), [150] * B)
+    for b in range(B):                       # layer 0 entries: same inputs on both sides
+        kd, vd = case.ver.kv_read(b, 0, 0, 150)
+        assert np.mean(kd.float().cpu().numpy() != case.caches[b].k[0][:150]) < 0.01
+        assert np.mean(vd.float().cpu().numpy() != case.caches[b].v[0][:150]) < 0.01
+    x0 = np.argmax(lo, axis=-1)
+    q = W.make_random_q((B, 1, k), V, 1.0, shape.seed)
+    drafts = W.sample_from(q, shape.seed).numpy()
+    u = W.make_uniforms((B, 1, k + 1), shape.seed)
+    r, g = case.step(x0, drafts, q, u)
+    err, exempt, diverged = compare_step(r, g, "bf16", k)
+    assert len(diverged) <= 1
+    case.close()
