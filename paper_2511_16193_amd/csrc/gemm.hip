@@ -394,8 +394,13 @@ __device__ __forceinline__ void gemm_bf16_ws_body(
             for (int i = 0; i < NT; ++i)
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wring[s % PD][i]),
-                                                                        af[s & 1][j], acc[i][j], 0, 0, 0);
+                    // gated form: weights first, so that a lane holds one row and consecutive features (what the
+                    // packed output wants); plain form: activations first, so that a lane holds one feature and the
+                    // 32 lanes of a half wave write 128 contiguous bytes of an output row
+                    acc[i][j] = GLU ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wring[s % PD][i]),
+                                                                              af[s & 1][j], acc[i][j], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][j], __builtin_bit_cast(bf16x8, wring[s % PD][i]),
+                                                                              acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             // refill the ring slot just consumed with the slice PD ahead (clamped at the end: a harmless
             // re-load).  Issued after the products that read the slot, so the slot's registers are dead and
@@ -479,20 +484,20 @@ __device__ __forceinline__ void gemm_bf16_ws_body(
         }
         return;
     }
+    // acc[i][j][4 q + r] <-> row m0 + 32 j + 8 q + 4 lg + r, feature n0 + 32 (wave NT + i) + l32
     float* dst = out + (int64_t)sp * M * N;
 #pragma unroll
-    for (int j = 0; j < MT; ++j) {
-        const int m = m0 + j * 32 + l32;
-        if (m < M) {
+    for (int i = 0; i < NT; ++i) {
+        const int n = n0 + (wave * NT + i) * 32 + l32;
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+        for (int j = 0; j < MT; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + (wave * NT + i) * 32 + 8 * q + 4 * lg;
-                    *reinterpret_cast<floatx4*>(dst + (int64_t)m * N + n) =
-                        floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + j * 32 + 8 * q + 4 * lg + r;
+                    if (m < M) dst[(int64_t)m * N + n] = acc[i][j][4 * q + r];
                 }
-        }
     }
 }
 
