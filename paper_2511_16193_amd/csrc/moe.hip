@@ -277,9 +277,11 @@ __global__ __launch_bounds__(256, 2) void moe_gemm_kernel(MoeArgs a) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    if (j < nt_here)
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wring[s % PD]),
-                                                                         af[s & 1][j], acc[j], 0, 0, 0);
+                    if (j < nt_here)      // MODE 1: rows first, so that a half wave stores 128 contiguous bytes of an output row
+                        acc[j] = MODE == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wring[s % PD]),
+                                                                                     af[s & 1][j], acc[j], 0, 0, 0)
+                                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][j], __builtin_bit_cast(bf16x8, wring[s % PD]),
+                                                                                     acc[j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 // refill the slot just consumed (after its readers, so the load lands in place)
                 const int ahead = slice + PD < kslices ? slice + PD : kslices - 1;
@@ -295,11 +297,12 @@ __global__ __launch_bounds__(256, 2) void moe_gemm_kernel(MoeArgs a) {
 #pragma unroll
             for (int j = 0; j < MT; ++j) {
                 if (j < nt_here) {
-                    float* dst = a.y + ((int64_t)(tile0 + g0 + j) * 32 + l32) * a.d + p * 128 + wave * 32 + 4 * lg;
+                    // acc[j][4 q + r] <-> padded row 32 (tile0 + g0 + j) + 8 q + 4 lg + r, feature 128 p + 32 wave + l32
+                    float* dst = a.y + ((int64_t)(tile0 + g0 + j) * 32 + 4 * lg) * a.d + p * 128 + wave * 32 + l32;
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        *reinterpret_cast<floatx4*>(dst + 8 * q) =
-                            floatx4{acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) dst[(int64_t)(8 * q + r) * a.d] = acc[j][4 * q + r];
                 }
             }
             __builtin_amdgcn_s_waitcnt(0xC07F);
