@@ -91,7 +91,7 @@ int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launch
  *   SV_OPT_GEMM_VARIANT  kernel / work-group tile of the bf16 projections (0..6; -1 = per shape, default)
  *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)
  *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for
- *   SV_OPT_ATTN_MAX_ROW_TILES  most 16-row tiles (1..4, default 3) one work-group of the bf16 attention takes;
+ *   SV_OPT_ATTN_MAX_ROW_TILES  most 16-row tiles (1..4, default 4) one work-group of the bf16 attention takes;
  *                           more stacked rows are split over row groups that stream the same keys
  *   SV_OPT_GRAPH  1 = verify_step replays its device work from a HIP graph captured on the second step with the
  *                 same batch shape and the same caller buffers (the first runs as plain launches); needs a context

@@ -330,7 +330,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     c->use_graph = false;
     c->graph_launch_shape = false;
     c->graph_clock = 0;
-    c->attn_max_rt = 3;            // four tiles leave the kernel short of registers (it spills)
+    c->attn_max_rt = 4;
     c->attn_chunk = kChunkKeys;
     c->attn_chunk_opt = 0;
     c->prof_mask = 0;
