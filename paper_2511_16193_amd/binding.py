@@ -27,6 +27,7 @@ EXPORTS = [
     "verify_kv_read", "verify_prefill", "verify_step",
     "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
     "sv_profile_read",
+    "sv_plan_accept_prob", "sv_plan_tau", "sv_plan_decoupled", "sv_plan_best_window", "sv_fit_affine",
 ]
 
 
@@ -52,6 +53,19 @@ class SvRuntime(C.Structure):
 class SvBatch(C.Structure):
     _fields_ = [("B", C.c_int32), ("k", C.c_int32), ("N", C.c_int32), ("seq_ids", C.POINTER(C.c_int32)),
                 ("last_tokens", C.c_void_p), ("draft_lens", C.c_void_p)]
+
+
+class SvAffine(C.Structure):
+    _fields_ = [("slope", C.c_double), ("icpt", C.c_double)]
+
+
+class SvPlanInput(C.Structure):
+    _fields_ = [("B", C.c_int), ("G", C.c_int), ("p", C.c_double), ("n_configs", C.c_int), ("g_v", C.POINTER(C.c_int)),
+                ("W", C.c_int), ("D", C.POINTER(SvAffine)), ("V", C.POINTER(SvAffine))]
+
+
+class SvPlan(C.Structure):
+    _fields_ = [("g_d", C.c_int), ("g_v", C.c_int), ("w", C.c_int), ("b", C.c_int), ("tgs", C.c_double)]
 
 
 class SvOut(C.Structure):
@@ -100,6 +114,14 @@ def load_library() -> C.CDLL:
     lib.sv_profile_enable.argtypes = [C.c_void_p, C.c_uint]
     lib.sv_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.sv_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
+    lib.sv_plan_accept_prob.restype = C.c_double
+    lib.sv_plan_accept_prob.argtypes = [C.c_double, C.c_int, C.c_int]
+    lib.sv_plan_tau.restype = C.c_double
+    lib.sv_plan_tau.argtypes = [C.c_double, C.c_int]
+    lib.sv_plan_decoupled.argtypes = [C.POINTER(SvPlanInput), C.POINTER(SvPlan)]
+    lib.sv_plan_best_window.argtypes = [C.c_double, SvAffine, C.POINTER(SvAffine), C.c_int, C.c_double,
+                                        C.POINTER(C.c_int), C.POINTER(C.c_double)]
+    lib.sv_fit_affine.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int, C.POINTER(SvAffine)]
     return lib
 
 
@@ -386,3 +408,47 @@ def op_sample(logits: torch.Tensor, drafts: torch.Tensor, draft_probs, uniforms,
     if rc != 0:
         raise SvError(rc, "sv_op_sample")
     return acc, toks, best
+
+
+# ---- planner (host-only entry points of specverify_plan.h) ----
+
+def plan_accept_prob(p: float, a: int, w: int) -> float:
+    return lib().sv_plan_accept_prob(p, a, w)
+
+
+def plan_tau(p: float, w: int) -> float:
+    return lib().sv_plan_tau(p, w)
+
+
+def fit_affine(bs, ts):
+    """(slope, icpt) of the least-squares line through the points."""
+    n = len(bs)
+    out = SvAffine()
+    rc = lib().sv_fit_affine((C.c_double * n)(*bs), (C.c_double * n)(*ts), n, C.byref(out))
+    if rc != 0:
+        raise SvError(rc, "sv_fit_affine: need two or more points with distinct batch sizes")
+    return out.slope, out.icpt
+
+
+def plan_decoupled(B: int, G: int, p: float, g_v, D, V, W: int) -> dict:
+    """Algorithm 1.  g_v: verifier configurations; D[g-1] = (slope, icpt) for g = 1..max(g_v);
+    V[c][w-1] = (slope, icpt) for configuration c and window w = 1..W."""
+    nc = len(g_v)
+    if len(D) < max(g_v) or len(V) != nc or any(len(v) != W for v in V):
+        raise ValueError("D needs max(g_v) entries, V one row of W entries per configuration")
+    inp = SvPlanInput(B, G, p, nc, (C.c_int * nc)(*g_v), W, (SvAffine * len(D))(*[SvAffine(*d) for d in D]),
+                      (SvAffine * (nc * W))(*[SvAffine(*x) for v in V for x in v]))
+    out = SvPlan()
+    rc = lib().sv_plan_decoupled(C.byref(inp), C.byref(out))
+    if rc != 0:
+        raise SvError(rc, "sv_plan_decoupled: invalid arguments")
+    return {"g_d": out.g_d, "g_v": out.g_v, "w": out.w, "b": out.b, "tgs": out.tgs}
+
+
+def plan_best_window(p: float, D, V, b: float):
+    W = len(V)
+    w, t = C.c_int(), C.c_double()
+    rc = lib().sv_plan_best_window(p, SvAffine(*D), (SvAffine * W)(*[SvAffine(*x) for x in V]), W, b, C.byref(w), C.byref(t))
+    if rc != 0:
+        raise SvError(rc, "sv_plan_best_window: invalid arguments")
+    return w.value, t.value

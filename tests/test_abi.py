@@ -11,7 +11,7 @@ LIB = os.path.join(ROOT, "paper_2511_16193_amd", "libspecverify.so")
 
 def declared_functions():
     names = []
-    for h in ("specverify.h", "specverify_ops.h"):
+    for h in ("specverify.h", "specverify_ops.h", "specverify_plan.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names += re.findall(r"\b((?:verify|sv)_[a-z0-9_]+)\s*\(", text)
