@@ -28,6 +28,17 @@ draft chains of k tokens each:
                appended is dead.  The emitted last token is NOT cached: it is
                the next step's x0.
 
+ 3'' match     (sampled exact match; what the paper's "exact token matching" and
+               its Fastest-of-N selection need to stay lossless with several
+               chains)  for every slot i the target's own token t_i is drawn from
+               p_i = softmax(logits_i / temperature) with randomness keyed by
+               (request, slot) only -- uniform u[b, 0, i-1], the same for every
+               chain -- and draft d_i is accepted iff d_i == t_i; at the first
+               mismatch r the emitted token is t_r, with none it is t_{k+1}.
+               Chains that agree with the sampled path see the same p_i and
+               hence the same t_i, so whichever chain is kept, the emitted
+               tokens are those of plain sampling with the same keys.
+
 Two ways of turning u_{k+1} into a token are defined (the paper fixes none):
  sample_mode 0  inverse CDF over ascending token id: smallest v whose running
                 sum of weights exceeds u * total.
@@ -50,6 +61,9 @@ one-hot q == exact-match sampling in law; temperature -> 0 == greedy; greedy
 verification == plain one-token-at-a-time decoding over chained steps
 including rollback; N chains under greedy: a = max_c match length, tokens
 unchanged.
+Match mode: the emitted tokens equal plain one-token-at-a-time sampling with
+the same keys, for any drafts and any number of chains, over chained steps with
+rollback; each emitted token follows the target's distribution (chi-square).
 Parity unpinned: which chain stochastic verification keeps when N > 1 (the
 longest-chain rule is not distribution preserving; only the greedy case has a
 ground truth) and the particular bit-mixing function of sample_mode 1 (pinned
@@ -65,6 +79,7 @@ from . import model as M
 
 GREEDY = 0
 STOCHASTIC = 1
+MATCH = 2
 SAMPLE_INVERSE_CDF = 0
 SAMPLE_EXP_RACE = 1
 
@@ -237,6 +252,31 @@ def verify_stochastic(logits: np.ndarray, drafts: np.ndarray, draft_probs: np.nd
     return ChainVerdict(a, tok, acc_margin, dmargin, zero_res)
 
 
+def verify_match(logits: np.ndarray, drafts: np.ndarray, slot_uniforms: np.ndarray, request: np.ndarray,
+                 temperature: float, sample_mode: int, draft_lens: np.ndarray | None = None) -> ChainVerdict:
+    """logits [S,k+1,V]; drafts [S,k]; slot_uniforms [S,k+1] = the (request, slot) keys, equal for the chains
+    of a request; request [S] = index of the request in the batch (the stream of sample_mode 1)."""
+    S, k1, V = logits.shape
+    k = k1 - 1
+    p = M.softmax(np.asarray(logits, dtype=np.float64) / temperature, axis=-1)
+    if sample_mode == SAMPLE_INVERSE_CDF:
+        t, tm = draw_inverse_cdf(p.reshape(S * k1, V), np.asarray(slot_uniforms, dtype=np.float64).reshape(-1))
+    elif sample_mode == SAMPLE_EXP_RACE:
+        t, tm = draw_exp_race(p.reshape(S * k1, V), np.asarray(slot_uniforms, dtype=np.float32).reshape(-1),
+                              np.repeat(np.asarray(request, dtype=np.uint64), k1))
+    else:
+        raise ValueError(sample_mode)
+    t, tm = t.reshape(S, k1), tm.reshape(S, k1)
+    match = drafts == t[:, :k]
+    if draft_lens is not None:
+        match = match & (np.arange(k)[None, :] < draft_lens[:, None])
+    a = leading_true(match) if k else np.zeros(S, dtype=np.int64)
+    tested = np.arange(k1)[None, :] <= a[:, None]                     # the draws of slots 1..a+1 decided something
+    acc_margin = np.min(np.where(tested, tm, np.inf), axis=-1)
+    rows = np.arange(S)
+    return ChainVerdict(a, t[rows, a], acc_margin, tm[rows, a], np.zeros(S, dtype=bool))
+
+
 # ------------------------------------------------------------- whole step ---
 
 @dataclass
@@ -280,6 +320,9 @@ def verify_step(spec: M.ModelSpec, weights: dict, caches, x0: np.ndarray, drafts
     flat_lens = None if draft_lens is None else np.repeat(np.asarray(draft_lens), N)
     if verify_mode == GREEDY:
         v = verify_greedy(flat_logits, flat_drafts, flat_lens)
+    elif verify_mode == MATCH:
+        slot_u = np.repeat(np.asarray(uniforms)[:, :1, :], N, axis=1).reshape(S, k + 1)    # chain 0's row keys every chain
+        v = verify_match(flat_logits, flat_drafts, slot_u, np.repeat(np.arange(B), N), temperature, sample_mode, flat_lens)
     else:
         flat_q = None if draft_probs is None else draft_probs.reshape(S, k, spec.vocab)
         stream = np.arange(S, dtype=np.uint64)          # b*N + chain

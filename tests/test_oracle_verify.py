@@ -366,3 +366,125 @@ def test_greedy_verification_reproduces_plain_decoding(n_chains):
                 assert np.max(np.abs(caches[b].v[l][:L] - ref[b][1].v[l][:L])) < 1e-9
     assert total_acc > 0                 # some drafts were accepted, some rejected
     assert total_acc < B * steps * k
+
+
+# ------------------------- match mode: sampled exact match, lossless for N chains ---
+
+@pytest.mark.parametrize("mode", [OV.SAMPLE_INVERSE_CDF, OV.SAMPLE_EXP_RACE])
+def test_match_mode_emits_the_target_law_whatever_the_drafts(mode):
+    """V = 16, k = 3, three chains with arbitrary drafts: the first emitted token follows p_1 and, given that
+    some chain carried the first token, the second follows that chain's p_2 (chi-square over 4*10^5 windows)."""
+    V, k, N, S = 16, 3, 3, 400_000
+    rng = np.random.default_rng(77)
+    base = rng.standard_normal((k + 1, V)) * 1.5                      # slot i's logits given the sampled path
+    other = rng.standard_normal((k + 1, V)) * 1.5                     # what a chain off the path would see
+    P = softmax(base)
+    drafts = rng.integers(0, V, size=(S, N, k))
+    u = rng.random((S, k + 1), dtype=np.float32)
+    # the sampled path of every window, by the draw functions on the true slot distributions; a chain sees the
+    # path's distribution at slot i+1 only if its first i drafts are on the path (slot 1 is always the true one)
+    req = np.arange(S)
+    t_path = np.empty((S, k + 1), dtype=np.int64)
+    for i in range(k + 1):
+        w = np.broadcast_to(P[i], (S, V))
+        if mode == OV.SAMPLE_INVERSE_CDF:
+            t_path[:, i], _ = OV.draw_inverse_cdf(w, u[:, i].astype(np.float64))
+        else:
+            t_path[:, i], _ = OV.draw_exp_race(w, u[:, i], req.astype(np.uint64))
+    verdicts = []
+    for c in range(N):
+        on_path = np.cumprod(drafts[:, c] == t_path[:, :k], axis=1).astype(bool)          # [S, k]
+        lg = np.empty((S, k + 1, V))
+        lg[:, 0] = base[0]
+        for i in range(1, k + 1):
+            lg[:, i] = np.where(on_path[:, i - 1][:, None], base[i], other[i])
+        verdicts.append(OV.verify_match(lg, drafts[:, c], u, req, 1.0, mode))
+    acc = np.stack([v.accepted for v in verdicts], axis=1)
+    best = np.argmax(acc, axis=1)
+    a = acc[req, best]
+    y = np.stack([v.token for v in verdicts], axis=1)[req, best]
+    out = np.where(np.arange(k + 1)[None, :] < a[:, None], drafts[req, best][:, list(range(k)) + [k - 1]], y[:, None])
+    # emitted tokens are the sampled path, as far as they go
+    for i in range(k + 1):
+        sel = a >= i
+        assert np.array_equal(out[sel, i], t_path[sel, i])
+    counts = np.bincount(out[:, 0], minlength=V)
+    chi2 = np.sum((counts - S * P[0]) ** 2 / (S * P[0]))
+    assert chi2 < stats.chi2.ppf(1 - ALPHA, V - 1)
+    sel = a >= 1
+    counts = np.bincount(out[sel, 1], minlength=V)
+    chi2 = np.sum((counts - sel.sum() * P[1]) ** 2 / (sel.sum() * P[1]))
+    assert chi2 < stats.chi2.ppf(1 - ALPHA, V - 1)
+    # three chains of uniform drafts: the first slot is carried with probability 1 - (1 - 1/V)^3 ... only if the
+    # drafts are independent of the path, which they are
+    want = 1 - (1 - 1 / V) ** N
+    z = (sel.mean() - want) / np.sqrt(want * (1 - want) / S)
+    assert abs(z) < 4.5
+
+
+def plain_sampled_continuation(spec, wn, cache, x0, keys, b, mode, temperature=1.0):
+    """One token at a time on a copy of the cache: token i is drawn from the target's distribution after the
+    prefix, with key (keys[i], request b)."""
+    import copy
+    c = copy.deepcopy(cache)
+    out, tok = [], int(x0)
+    for u in keys:
+        lg = M.forward(spec, wn, [c], np.array([[tok]]), np.array([[c.length]]), np.ones((1, 1, 1), dtype=bool))
+        c.length += 1
+        p = softmax(lg[0, 0] / temperature)[None, :]
+        if mode == OV.SAMPLE_INVERSE_CDF:
+            t, _ = OV.draw_inverse_cdf(p, np.array([u], dtype=np.float64))
+        else:
+            t, _ = OV.draw_exp_race(p, np.array([u], dtype=np.float32), np.array([b], dtype=np.uint64))
+        tok = int(t[0])
+        out.append(tok)
+    return out, c
+
+
+@pytest.mark.parametrize("n_chains,mode", [(1, OV.SAMPLE_EXP_RACE), (3, OV.SAMPLE_EXP_RACE), (3, OV.SAMPLE_INVERSE_CDF)])
+def test_match_verification_reproduces_plain_sampling(n_chains, mode):
+    """Tiny fp32 model, B = 3 prompts, k = 4, six chained steps with rollback.  Chains agree with the sampled
+    path for a random number of tokens and then wander off.  Whatever they hold, the emitted stream equals
+    plain sampling with the same (request, slot) keys, the accepted length is the longest agreement, the lowest
+    such chain is kept, and the cache equals the plain decoder's."""
+    shape = W.scaled_down(W.CONFIGS["cfg1"], batch=3)
+    spec = spec_of(shape)
+    wn = W.weights_to_numpy(W.make_weights(shape))
+    B, k, steps = 3, 4, 6
+    prompts = W.make_tokens((B, 40), shape.vocab, shape.seed, "prompt")
+    rng = np.random.default_rng(5 + n_chains)
+    caches = [M.SeqCache(spec, 40 + steps * (k + 1) + n_chains * k + 4) for _ in range(B)]
+    x0 = np.empty(B, dtype=np.int64)
+    for b in range(B):
+        x0[b] = int(np.argmax(OV.prefill(spec, wn, caches[b], prompts[b])[-1]))
+    for step in range(steps):
+        u = rng.random((B, n_chains, k + 1), dtype=np.float32)
+        path, ref_caches = [], []
+        for b in range(B):
+            t, c = plain_sampled_continuation(spec, wn, caches[b], x0[b], u[b, 0], b, mode)
+            path.append(t)
+            ref_caches.append(c)
+        drafts = rng.integers(0, shape.vocab, size=(B, n_chains, k))
+        agree = rng.integers(0, k + 1, size=(B, n_chains))
+        if step == 2:
+            agree[:] = k                                              # everything accepted once
+        if step == 3:
+            agree[:] = 0
+        for b in range(B):
+            for c in range(n_chains):
+                drafts[b, c, :agree[b, c]] = path[b][:agree[b, c]]
+                if agree[b, c] < k and drafts[b, c, agree[b, c]] == path[b][agree[b, c]]:
+                    drafts[b, c, agree[b, c]] = (drafts[b, c, agree[b, c]] + 1) % shape.vocab
+        r = OV.verify_step(spec, wn, caches, x0, drafts, None, u, verify_mode=OV.MATCH, sample_mode=mode)
+        for b in range(B):
+            a = int(r.accepted_len[b])
+            assert a == int(agree[b].max())
+            assert int(r.best_chain[b]) == int(np.argmax(agree[b]))
+            assert [int(t) for t in r.out_tokens[b, : a + 1]] == path[b][: a + 1]
+            assert np.all(r.out_tokens[b, a + 1:] == -1)
+            L = caches[b].length
+            assert L == ref_caches[b].length - (k + 1) + a + 1
+            for l in range(spec.n_layers):
+                assert np.max(np.abs(caches[b].k[l][:L] - ref_caches[b].k[l][:L])) < 1e-9
+                assert np.max(np.abs(caches[b].v[l][:L] - ref_caches[b].v[l][:L])) < 1e-9
+            x0[b] = path[b][a]
