@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--drafts", choices=["noisy-target", "independent"], default="noisy-target",
                     help="independent: drafts from q = softmax(N(0,1)) without any device decoding step, so that "
                          "every kernel launch of the process has the timed step's shape (used for profiles)")
+    ap.add_argument("--verify", choices=["config", "greedy", "stochastic", "match"], default="config",
+                    help="verification rule (default: the configuration's); with `match` the synthetic drafts are "
+                         "rarely accepted: use it to time the rule, not for the headline figure")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps run one plain elementwise pass that reads 1 GiB and writes 1 GiB "
                          "(torch.neg(src, out=dst) on fp32, an op nothing else in the run uses), the known-size kernel against which the HBM byte "
@@ -142,7 +145,8 @@ def main():
     shape = W.CONFIGS[args.config]
     if args.batch is not None:
         shape = W.scaled_down(shape, batch=args.batch)
-    case = DeviceCase(shape, k=args.k, log=log)
+    vmode = {"config": None, "greedy": 0, "stochastic": 1, "match": 2}[args.verify]
+    case = DeviceCase(shape, k=args.k, verify_mode=vmode, log=log)
     if args.gemm_variant is not None:
         case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
     if args.attn_chunk is not None:
@@ -271,7 +275,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": shape.name + (f" at batch {B}" if args.batch is not None else ""), "batch": B, "k": k, "chains": N, "rows_per_step": T,
                    "prefix_tokens": int(case.lengths.sum()), "drafts": args.drafts, "draft_sigma": list(shape.draft_sigma) if args.sigma is None else [args.sigma],
-                   "verify": "stochastic, exponential-race draw, temperature 1.0"},
+                   "verify": {None: "greedy" if shape.verify_mode == 0 else "stochastic, exponential-race draw, temperature 1.0",
+                              0: "greedy", 1: "stochastic, exponential-race draw, temperature 1.0",
+                              2: "sampled exact match, exponential-race draw, temperature 1.0"}[vmode]},
         "accepted_drafts_per_step": int(acc.sum()), "emitted_tokens_per_step": emitted,
         "accepted_drafts_tokens_per_s": int(acc.sum()) / (ms_per_step * 1e-3),
         "roofline": dominant, "roofline_other": other,

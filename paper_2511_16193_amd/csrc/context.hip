@@ -104,7 +104,7 @@ bool make_layout(const sv_model& m, const sv_runtime& r, Layout& L) {
     L.chain_acc = take(sizeof(int32_t) * r.max_batch * r.max_chains);
     L.chain_tok = take(sizeof(int32_t) * r.max_batch * r.max_chains);
     L.chain_row = take(sizeof(int32_t) * r.max_batch * r.max_chains);
-    L.draw_part = take(sizeof(float) * 4 * kDrawParts * r.max_batch * r.max_chains);
+    L.draw_part = take(sizeof(float) * 4 * kDrawParts * T);       // per (request, chain); per row in match mode
     L.rope = take(sizeof(float) * (size_t)T * m.head_dim);
     L.row_stat = take(sizeof(float) * 4 * T);
     L.h = take(sizeof(float) * (size_t)T * m.d_model);
@@ -282,7 +282,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     if (!r->kv_pool || !r->workspace || r->kv_pool_bytes < verify_kv_pool_bytes(m, r) || r->workspace_bytes < L.total ||
         ((uintptr_t)r->kv_pool & 255) || ((uintptr_t)r->workspace & 255))
         return SV_EINVAL;
-    if (!(r->temperature > 0.f) || r->verify_mode < 0 || r->verify_mode > 1 || r->sample_mode < 0 || r->sample_mode > 1)
+    if (!(r->temperature > 0.f) || r->verify_mode < 0 || r->verify_mode > 2 || r->sample_mode < 0 || r->sample_mode > 1)
         return SV_EINVAL;
     if (!w->embed || !w->lm_head || !w->final_norm || !w->ln1 || !w->wqkv || !w->wo || !w->ln2 || !w->w_gate_up || !w->w_down)
         return SV_EINVAL;
@@ -803,7 +803,7 @@ extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts,
         return c->fail(SV_EINVAL, "batch %d / k %d / chains %d outside the limits given at init", B, k, N);
     if (!bt->seq_ids || !bt->last_tokens || (k > 0 && !drafts) || !out->accepted_len || !out->out_tokens || !out->best_chain)
         return c->fail(SV_EINVAL, "null argument");
-    if (c->rt.verify_mode == SV_STOCHASTIC && !uniforms) return c->fail(SV_EINVAL, "stochastic verification needs uniforms");
+    if (c->rt.verify_mode != SV_GREEDY && !uniforms) return c->fail(SV_EINVAL, "stochastic and match verification need uniforms");
     const int n = 1 + N * k;
     SV_TRY(stage_batch(c, bt->seq_ids, B, n));
     int max_ub = 0;
@@ -850,7 +850,7 @@ extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const fl
                             float temperature, void* scratch, int32_t* accepted_len, int32_t* out_tokens,
                             int32_t* best_chain, void* stream) {
     if (!logits || (k > 0 && !drafts) || !scratch || !accepted_len || !out_tokens || !best_chain || B <= 0 || N <= 0 ||
-        k < 0 || V <= 0 || !(temperature > 0.f) || (verify_mode == SV_STOCHASTIC && !uniforms))
+        k < 0 || V <= 0 || !(temperature > 0.f) || verify_mode < 0 || verify_mode > 2 || (verify_mode != SV_GREEDY && !uniforms))
         return SV_EINVAL;
     const int T = B * (1 + N * k), S = B * N;
     char* p = reinterpret_cast<char*>(scratch);
@@ -869,7 +869,7 @@ extern "C" int sv_op_sample(const float* logits, const int32_t* drafts, const fl
 extern "C" size_t sv_op_sample_scratch_bytes(int B, int N, int k) {
     if (B <= 0 || N <= 0 || k < 0) return 0;
     return align_up(sizeof(float) * 4 * (size_t)B * (1 + N * k)) + 3 * align_up(sizeof(int32_t) * (size_t)B * N) +
-           align_up(sizeof(float) * 4 * kDrawParts * (size_t)B * N);
+           align_up(sizeof(float) * 4 * kDrawParts * (size_t)B * (1 + N * k));      // match mode draws per row
 }
 
 struct MoeScratch { size_t ids, w, cnt, off, perm, inv, act, y, logits, total; };

@@ -81,6 +81,8 @@ __global__ void accept_kernel(SampleArgs a) {
         bool ok;
         if (a.verify_mode == 0) {
             ok = x == __float_as_int(a.row_stat[row * 4 + 2]);
+        } else if (a.verify_mode == 2) {
+            ok = x == __float_as_int(a.row_stat[row * 4 + 3]);       // the token drawn for this slot
         } else {
             const float m = a.row_stat[row * 4], sum = a.row_stat[row * 4 + 1];
             const float p = expf((a.logits[(int64_t)row * a.V + x] - m) * inv_temp) / sum;
@@ -94,6 +96,7 @@ __global__ void accept_kernel(SampleArgs a) {
     const int row = slot_row(b, c, acc + 1, n, a.k);
     a.chain_row[s] = row;
     if (a.verify_mode == 0) a.chain_tok[s] = __float_as_int(a.row_stat[row * 4 + 2]);
+    if (a.verify_mode == 2) a.chain_tok[s] = __float_as_int(a.row_stat[row * 4 + 3]);
 }
 
 __device__ __forceinline__ uint64_t splitmix_finalise(uint64_t z) {
@@ -102,21 +105,30 @@ __device__ __forceinline__ uint64_t splitmix_finalise(uint64_t z) {
     return z ^ (z >> 31);
 }
 
-// Final draw of one (request, chain).  Stochastic mode only.
+// Draw of one token.  ROWS == false (stochastic verification): the final draw of one (request, chain), from the
+// residual after a rejection or from the bonus row.  ROWS == true (match verification): the target's own token of
+// one logits row, i.e. of one draft slot, from that row's distribution; the randomness is keyed by the request's
+// index in the batch and the slot alone (the uniform of chain 0), so every chain of a request is held to the same
+// token at the same slot.  The result goes to row_stat[row][3].
+template <bool ROWS>
 __global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
-    const int s = blockIdx.x;
-    const int b = s / a.N;
+    const int s = blockIdx.x;                             // (request, chain), or logits row
+    const int n = 1 + a.N * a.k;
+    const int b = ROWS ? s / n : s / a.N;
     const int klim = a.draft_lens ? min(a.draft_lens[b], a.k) : a.k;
-    const int acc = a.chain_acc[s];
-    const bool rejected = acc < klim;
-    const int row = a.chain_row[s];
+    const int acc = ROWS ? 0 : a.chain_acc[s];
+    const bool rejected = ROWS ? false : acc < klim;
+    const int row = ROWS ? s : a.chain_row[s];
     const float* lrow = a.logits + (int64_t)row * a.V;
     const float* qrow = (rejected && a.draft_probs) ? a.draft_probs + ((int64_t)s * a.k + acc) * a.V : nullptr;
     const int xrej = rejected ? a.drafts[(int64_t)s * a.k + acc] : -1;
     const float inv_temp = 1.0f / a.temperature;
     const float m = a.row_stat[row * 4], sum = a.row_stat[row * 4 + 1];
     const float log_sum = logf(sum);
-    const float u = a.uniforms[(int64_t)s * (a.k + 1) + a.k];
+    // slot served by row j of a request: row 0 -> slot 1, the row of draft i of any chain -> slot i + 1
+    const int j = s % n;
+    const int slot = j == 0 ? 1 : (j - 1) % max(a.k, 1) + 2;
+    const float u = ROWS ? a.uniforms[(int64_t)b * a.N * (a.k + 1) + (slot - 1)] : a.uniforms[(int64_t)s * (a.k + 1) + a.k];
     const int V = a.V;
 
     auto prob = [&](int v) { return expf((lrow[v] - m) * inv_temp) / sum; };
@@ -129,7 +141,7 @@ __global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
     if (a.sample_mode == 1) {
         // exponential race: argmax_v ln w_v - ln e_v ; track the residual's winner and, for the case that
         // the residual is identically zero, the winner under p as well.
-        const uint64_t key = ((uint64_t)(uint32_t)s << 32) | (uint64_t)__float_as_uint(u);
+        const uint64_t key = ((uint64_t)(uint32_t)(ROWS ? b : s) << 32) | (uint64_t)__float_as_uint(u);
         float best_r = -INFINITY, best_p = -INFINITY;
         int arg_r = 0x7fffffff, arg_p = 0x7fffffff;
         // the vocabulary is cut into gridDim.y contiguous parts; each work-group finds the winners of its part
@@ -221,7 +233,9 @@ __global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
             run += (double)w;
             if (run > target) { tok = v; break; }
         }
-        a.chain_tok[s] = tok >= 0 ? tok : last_pos;
+        const int drawn = tok >= 0 ? tok : last_pos;
+        if (ROWS) a.row_stat[row * 4 + 3] = __int_as_float(drawn);
+        else a.chain_tok[s] = drawn;
     }
 }
 
@@ -265,13 +279,15 @@ __global__ void commit_len_kernel(RollbackArgs r) {
     if (b < r.B) r.seq_len[r.batch_seq[b]] += r.accepted_len[b] + 1;
 }
 
-// Winner of a chain's exponential race over the parts of the vocabulary (larger score; lower id among equals).
+// Winner of a chain's (or, ROWS, a row's) exponential race over the parts of the vocabulary (larger score; lower
+// id among equals).
+template <bool ROWS>
 __global__ void draw_reduce_kernel(SampleArgs a, int parts) {
     const int s = blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= a.B * a.N) return;
-    const int b = s / a.N;
+    if (s >= (ROWS ? a.B * (1 + a.N * a.k) : a.B * a.N)) return;
+    const int b = ROWS ? 0 : s / a.N;
     const int klim = a.draft_lens ? min(a.draft_lens[b], a.k) : a.k;
-    const bool rejected = a.chain_acc[s] < klim;
+    const bool rejected = ROWS ? false : a.chain_acc[s] < klim;
     float best_r = -INFINITY, best_p = -INFINITY;
     int arg_r = 0x7fffffff, arg_p = 0x7fffffff;
     for (int i = 0; i < parts; ++i) {
@@ -281,19 +297,29 @@ __global__ void draw_reduce_kernel(SampleArgs a, int parts) {
         if (r > best_r || (r == best_r && ar < arg_r)) { best_r = r; arg_r = ar; }
         if (p > best_p || (p == best_p && ap < arg_p)) { best_p = p; arg_p = ap; }
     }
-    a.chain_tok[s] = (rejected && best_r > -INFINITY) ? arg_r : arg_p;
+    const int drawn = (rejected && best_r > -INFINITY) ? arg_r : arg_p;
+    if (ROWS) a.row_stat[s * 4 + 3] = __int_as_float(drawn);
+    else a.chain_tok[s] = drawn;
 }
 
 hipError_t sample_verify(const SampleArgs& a, hipStream_t st) {
     const int T = a.B * (1 + a.N * a.k), S = a.B * a.N;
     hipLaunchKernelGGL(row_stats_kernel, dim3(T), dim3(NT), 0, st, a.logits, a.row_stat, a.V, 1.0f / a.temperature);
-    hipLaunchKernelGGL(accept_kernel, dim3((S + 63) / 64), dim3(64), 0, st, a);
-    if (a.verify_mode != 0) {
-        if (a.sample_mode == 1) {      // the race's per-id arithmetic dominates: spread every chain over several work-groups
-            hipLaunchKernelGGL(draw_kernel, dim3(S, kDrawParts), dim3(NT), 0, st, a);
-            hipLaunchKernelGGL(draw_reduce_kernel, dim3((S + 63) / 64), dim3(64), 0, st, a, kDrawParts);
+    if (a.verify_mode == 2) {          // match: the target's token of every slot first, then the comparison
+        if (a.sample_mode == 1) {
+            hipLaunchKernelGGL(draw_kernel<true>, dim3(T, kDrawParts), dim3(NT), 0, st, a);
+            hipLaunchKernelGGL(draw_reduce_kernel<true>, dim3((T + 63) / 64), dim3(64), 0, st, a, kDrawParts);
         } else {
-            hipLaunchKernelGGL(draw_kernel, dim3(S), dim3(NT), 0, st, a);
+            hipLaunchKernelGGL(draw_kernel<true>, dim3(T), dim3(NT), 0, st, a);
+        }
+    }
+    hipLaunchKernelGGL(accept_kernel, dim3((S + 63) / 64), dim3(64), 0, st, a);
+    if (a.verify_mode == 1) {
+        if (a.sample_mode == 1) {      // the race's per-id arithmetic dominates: spread every chain over several work-groups
+            hipLaunchKernelGGL(draw_kernel<false>, dim3(S, kDrawParts), dim3(NT), 0, st, a);
+            hipLaunchKernelGGL(draw_reduce_kernel<false>, dim3((S + 63) / 64), dim3(64), 0, st, a, kDrawParts);
+        } else {
+            hipLaunchKernelGGL(draw_kernel<false>, dim3(S), dim3(NT), 0, st, a);
         }
     }
     hipLaunchKernelGGL(select_kernel, dim3((a.B + 63) / 64), dim3(64), 0, st, a);

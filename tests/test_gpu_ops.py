@@ -137,6 +137,10 @@ def oracle_sample(logits, drafts, q, u, verify_mode, sample_mode, temperature, d
     lens = None if draft_lens is None else np.repeat(draft_lens, N)
     if verify_mode == OV.GREEDY:
         v = OV.verify_greedy(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k), lens)
+    elif verify_mode == OV.MATCH:
+        v = OV.verify_match(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
+                            np.repeat(u[:, :1, :], N, axis=1).reshape(S, k + 1), np.repeat(np.arange(B), N),
+                            temperature, sample_mode, lens)
     else:
         v = OV.verify_stochastic(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
                                  None if q is None else q.numpy().reshape(S, k, V), u.reshape(S, k + 1),
@@ -188,6 +192,49 @@ def test_sampler_matches_oracle_on_given_logits(B, N, k, V, vmode, smode, temp, 
         assert margin[b] < 1e-5, (b, ga[b], a[b], gout[b], out[b], margin[b])
     assert len(bad) <= max(1, B // 8)
     assert a.max() > 0 or k == 0 or not with_q or ragged
+
+
+@pytest.mark.parametrize("B,N,k,V,smode,temp,ragged", [
+    (6, 3, 4, 2048, OV.SAMPLE_EXP_RACE, 1.0, False),
+    (6, 3, 4, 2048, OV.SAMPLE_INVERSE_CDF, 0.8, True),
+    (5, 1, 8, 4099, OV.SAMPLE_EXP_RACE, 1.0, True),
+    (4, 1, 0, 2048, OV.SAMPLE_EXP_RACE, 1.0, False),            # k = 0: plain sampling of one token
+    (8, 2, 4, 152064, OV.SAMPLE_EXP_RACE, 1.0, False),          # full vocabulary
+])
+def test_sampler_match_mode_on_given_logits(B, N, k, V, smode, temp, ragged):
+    """Sampled exact match on identical fp32 logits: the tokens the oracle draws for the slots are planted into
+    the drafts with probability 0.6, so chains agree with them for a while; accepted lengths, kept chain and tokens
+    must be identical except where the oracle's own draw margin is below 1e-5."""
+    from paper_2511_16193_amd import op_sample
+    logits, drafts, _, u = random_case(B, N, k, V, 300 + B + k + V % 5, with_q=False)
+    rng = np.random.default_rng(9)
+    if k:
+        # the token of every row under the (request, slot) key
+        n = 1 + N * k
+        p = M.softmax(logits.astype(np.float64) / temp, axis=-1).reshape(B * n, V)
+        slot = np.array([0] + [i + 1 for _ in range(N) for i in range(k)])           # slot index - 1 served by row j
+        uu = u[:, 0, :][:, slot].reshape(-1)
+        if smode == OV.SAMPLE_INVERSE_CDF:
+            t, _ = OV.draw_inverse_cdf(p, uu.astype(np.float64))
+        else:
+            t, _ = OV.draw_exp_race(p, uu.astype(np.float32), np.repeat(np.arange(B, dtype=np.uint64), n))
+        t = t.reshape(B, n)
+        for c in range(N):
+            rows = np.concatenate([t[:, :1], t[:, 1 + c * k: 1 + (c + 1) * k]], axis=1)[:, :k]
+            drafts[:, c] = np.where(rng.random((B, k)) < 0.6, rows, drafts[:, c])
+    lens = rng.integers(0, k + 1, B) if ragged else None
+    a, out, best, margin = oracle_sample(logits, drafts, None, u, OV.MATCH, smode, temp, lens)
+    ga, gout, gbest = op_sample(
+        torch.from_numpy(logits).to(DEV), torch.from_numpy(drafts).to(torch.int32).to(DEV).contiguous(), None,
+        torch.from_numpy(u).to(DEV), verify_mode=OV.MATCH, sample_mode=smode, temperature=temp,
+        draft_lens=None if lens is None else torch.from_numpy(lens).to(torch.int32).to(DEV))
+    torch.cuda.synchronize()
+    ga, gout, gbest = ga.cpu().numpy(), gout.cpu().numpy(), gbest.cpu().numpy()
+    bad = [b for b in range(B) if not (ga[b] == a[b] and gbest[b] == best[b] and np.array_equal(gout[b], out[b]))]
+    for b in bad:
+        assert margin[b] < 1e-5, (b, ga[b], a[b], gout[b], out[b], margin[b])
+    assert len(bad) <= max(1, B // 8)
+    assert k == 0 or a.max() > 0
 
 
 def test_sampler_zero_residual_falls_back_to_target():

@@ -77,6 +77,9 @@ SMALL_BF16 = W.Shape("small-bf16", 3, 256, 8, 2, 128, 512, 2048, dtype="bf16", b
     (8, 3, OV.GREEDY, 0, True),                          # 100 stacked rows: two row groups of 4 tiles (the 32B
                                                          # configuration's three chains of eight drafts)
     (-4, 1, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),    # k = 4 with ragged draft windows (0..4 per request)
+    (3, 3, OV.MATCH, OV.SAMPLE_EXP_RACE, True),          # sampled exact match, three chains
+    (4, 1, OV.MATCH, OV.SAMPLE_INVERSE_CDF, True),
+    (-4, 2, OV.MATCH, OV.SAMPLE_EXP_RACE, True),         # ... with ragged windows
 ])
 def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed):
     """bf16 decoder small enough for the oracle (3 layers, d 256, 8 q / 2 kv heads x 128, vocab 2048) over a
@@ -115,8 +118,26 @@ def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed)
                     if i < 1 + b % k:
                         drafts[b, (b + step) % n_chains, i] = tok
         u = W.make_uniforms((B, n_chains, k + 1), shape.seed + step)
+        if vmode == OV.MATCH and k:
+            # ... and match verification: the oracle's own sampled continuation under the (request, slot) keys
+            import copy
+            for b in range(B):
+                c = copy.deepcopy(case.caches[b])
+                tok = int(x0[b])
+                for i in range(k):
+                    lg = M.forward(case.spec, case.wn, [c], np.array([[tok]]), np.array([[c.length]]),
+                                   np.ones((1, 1, 1), dtype=bool))
+                    c.length += 1
+                    p = M.softmax(lg[0, :1], axis=-1)
+                    if smode == OV.SAMPLE_INVERSE_CDF:
+                        t, _ = OV.draw_inverse_cdf(p, np.array([u[b, 0, i]], dtype=np.float64))
+                    else:
+                        t, _ = OV.draw_exp_race(p, np.array([u[b, 0, i]], dtype=np.float32), np.array([b], dtype=np.uint64))
+                    tok = int(t[0])
+                    if i < 1 + b % k:
+                        drafts[b, (b + step) % n_chains, i] = tok
         lens = np.array([(b + step) % (k + 1) for b in range(B)], dtype=np.int64) if ragged else None
-        r, g = case.step(x0, drafts, q if vmode == OV.STOCHASTIC else None, u if vmode == OV.STOCHASTIC else None,
+        r, g = case.step(x0, drafts, q if vmode == OV.STOCHASTIC else None, u if vmode != OV.GREEDY else None,
                          draft_lens=lens)
         if ragged:
             assert np.all(g["accepted_len"] <= lens)
