@@ -24,7 +24,7 @@ SV_PROF_GEMM, SV_PROF_ATTENTION, SV_PROF_SAMPLER, SV_PROF_ROLLBACK, SV_PROF_MOE 
 EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
-    "verify_kv_read", "verify_prefill", "verify_step",
+    "verify_kv_read", "verify_prefill", "verify_prefill_batch", "verify_step",
     "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
     "sv_profile_read",
     "sv_plan_accept_prob", "sv_plan_tau", "sv_plan_decoupled", "sv_plan_best_window", "sv_fit_affine",
@@ -95,6 +95,8 @@ def load_library() -> C.CDLL:
     lib.verify_kv_write.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.verify_kv_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.verify_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.verify_prefill_batch.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_int32,
+                                         C.POINTER(C.c_int32), C.c_void_p]
     lib.verify_step.argtypes = [C.c_void_p, C.POINTER(SvBatch), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(SvOut)]
     lib.sv_op_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.c_int, C.c_void_p]
@@ -247,6 +249,23 @@ class Verifier:
         out = torch.empty(self.vocab, dtype=torch.float32, device=self.device) if want_logits else None
         self._check(self.lib.verify_prefill(self.ctx, seq_id, _ptr(tokens), tokens.numel(), _ptr(out)))
         return out
+
+    def prefill_batch(self, seq_ids, tokens: torch.Tensor, lens, want_logits: bool = True):
+        """tokens int32 [B, ld] (row b = prompt of seq_ids[b], lens[b] tokens long); any order: the rows are
+        handed over longest first and the logits returned in the caller's order."""
+        B = len(seq_ids)
+        order = sorted(range(B), key=lambda b: -int(lens[b]))
+        tokens = tokens.to(device=self.device, dtype=torch.int32)
+        tok = tokens[torch.as_tensor(order, device=self.device)].contiguous()
+        ids = (C.c_int32 * B)(*[int(seq_ids[b]) for b in order])
+        n = (C.c_int32 * B)(*[int(lens[b]) for b in order])
+        out = torch.empty((B, self.vocab), dtype=torch.float32, device=self.device) if want_logits else None
+        self._check(self.lib.verify_prefill_batch(self.ctx, ids, B, _ptr(tok), tok.shape[1], n, _ptr(out)))
+        if out is None:
+            return None
+        inv = torch.empty(B, dtype=torch.long)
+        inv[torch.as_tensor(order)] = torch.arange(B)
+        return out[inv.to(self.device)]
 
     # -- the step --
     def step(self, seq_ids, last_tokens: torch.Tensor, drafts: torch.Tensor | None, draft_probs: torch.Tensor | None,

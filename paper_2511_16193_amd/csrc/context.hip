@@ -183,6 +183,9 @@ struct sv_ctx {
     bool staged_valid[kRing];
     int ring_pos;
     int n_work;                                           // attention work items staged for the current batch
+    const int32_t* tok_matrix = nullptr;                  // batched prefill: the prompts the next forward pass reads its rows from
+    const int32_t* tok_len = nullptr;
+    int tok_ld = 0, tok_col0 = 0;
     int gemm_variant;                                     // -1 = choose per shape
     bool packed;                                          // projection weights are in fragment order
     bool attn_generic;
@@ -604,6 +607,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
     rp.row_tok = c->at<int32_t>(L.row_tok); rp.row_pos = c->at<int32_t>(L.row_pos); rp.row_slot = c->at<int32_t>(L.row_slot);
     rp.rope = c->at<float>(L.rope);
     rp.B = B; rp.n = n; rp.k = k; rp.head_dim = m.head_dim; rp.rope_theta = m.rope_theta;
+    rp.tok_matrix = c->tok_matrix; rp.tok_len = c->tok_len; rp.tok_ld = c->tok_ld; rp.tok_col0 = c->tok_col0;
     SV_HIP(c, prep_rows(rp, st));
     SV_HIP(c, embed_rows(c->embed, m.dtype, rp.row_tok, h, T, d, st));
 
@@ -700,6 +704,61 @@ extern "C" int verify_prefill(sv_ctx* c, int32_t id, const int32_t* tokens, int3
         if (done == n && last_logits)
             SV_HIP(c, hipMemcpyAsync(last_logits, c->at<float>(c->lay.logits) + (size_t)(cn - 1) * c->model.vocab,
                                      sizeof(float) * c->model.vocab, hipMemcpyDeviceToDevice, c->stream));
+    }
+    return SV_OK;
+}
+
+// Prompts of several sequences at once.  Pass p covers tokens p*c .. p*c+c-1 of every prompt that is that long
+// (the prompts come longest first, so those are the first B_act of them): B_act * c rows through the same kernels as
+// a verification step -- a chunk is x0 plus one chain of c-1 "drafts", causal visibility, every row kept -- with
+// c the rows per request the workspace was sized for (1 + max_chains * max_k; at most 256 / G so that the rows of
+// a kv head fit the attention kernel's tiles).  Rows past the end of a shorter prompt are padding: they sit
+// behind the real rows, which therefore never see them, their cache entries lie beyond the new length, and
+// the length advances by the real count.
+extern "C" int verify_prefill_batch(sv_ctx* c, const int32_t* seq_ids, int32_t B, const int32_t* tokens, int32_t ld,
+                                    const int32_t* n, float* last_logits) {
+    if (!c || !seq_ids || !tokens || !n) return SV_EINVAL;
+    if (B <= 0 || B > c->rt.max_batch || ld <= 0) return c->fail(SV_EINVAL, "prefill of %d prompts (limit %d), row pitch %d", B, c->rt.max_batch, ld);
+    for (int b = 0; b < B; ++b) {
+        if (n[b] <= 0 || n[b] > ld) return c->fail(SV_EINVAL, "prompt %d has %d tokens (row pitch %d)", b, n[b], ld);
+        if (b && n[b] > n[b - 1]) return c->fail(SV_EINVAL, "prompts must come longest first (prompt %d: %d after %d)", b, n[b], n[b - 1]);
+        const int id = seq_ids[b];
+        if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
+        if (pages_for(c, c->seqs[id].len_ub + n[b] + c->lay.T / c->rt.max_batch) > c->rt.max_pages_per_seq)
+            return c->fail(SV_ENOPAGES, "sequence %d would exceed max_pages_per_seq", id);
+    }
+    const int G = c->model.n_q_heads / c->model.n_kv_heads;
+    const int width_max = std::max(1, std::min(c->lay.T / c->rt.max_batch, 256 / G));
+    int32_t* len_dev = c->at<int32_t>(c->lay.chain_acc);          // free outside a verification step
+    {   // the lengths travel through a slot of the pinned staging ring, like a batch's ids
+        const int slot = c->ring_pos;
+        if (c->staged_valid[slot]) SV_HIP(c, hipEventSynchronize(c->staged[slot]));
+        for (int b = 0; b < B; ++b) c->staging[slot][b] = n[b];
+        SV_HIP(c, hipMemcpyAsync(len_dev, c->staging[slot], sizeof(int32_t) * B, hipMemcpyHostToDevice, c->stream));
+        SV_HIP(c, hipEventRecord(c->staged[slot], c->stream));
+        c->staged_valid[slot] = true;
+        c->ring_pos = (slot + 1) % kRing;
+    }
+    for (int col0 = 0; col0 < n[0]; col0 += width_max) {
+        int B_act = 0;
+        while (B_act < B && n[B_act] > col0) ++B_act;
+        const int width = std::min(width_max, n[0] - col0);
+        SV_TRY(stage_batch(c, seq_ids, B_act, width));
+        int max_ub = 0;
+        for (int b = 0; b < B_act; ++b) max_ub = std::max(max_ub, c->seqs[seq_ids[b]].len_ub);
+        c->tok_matrix = tokens; c->tok_len = len_dev; c->tok_ld = ld; c->tok_col0 = col0;
+        const int rc = forward_rows(c, B_act, width, width - 1, nullptr, nullptr, max_ub);
+        c->tok_matrix = nullptr; c->tok_len = nullptr;
+        if (rc != SV_OK) return rc;
+        SV_HIP(c, add_len_ragged(c->at<int32_t>(c->lay.seq_len), c->at<int32_t>(c->lay.batch_seq), B_act, len_dev, col0, width, c->stream));
+        for (int b = 0; b < B_act; ++b) {
+            const int real = std::min(width, n[b] - col0);
+            c->seqs[seq_ids[b]].len_ub += real;
+            if (last_logits && n[b] <= col0 + width)              // this pass holds the prompt's last token
+                SV_HIP(c, hipMemcpyAsync(last_logits + (size_t)b * c->model.vocab,
+                                         c->at<float>(c->lay.logits) + ((size_t)b * width + real - 1) * c->model.vocab,
+                                         sizeof(float) * c->model.vocab, hipMemcpyDeviceToDevice, c->stream));
+        }
     }
     return SV_OK;
 }

@@ -14,7 +14,12 @@ __global__ void prep_rows_kernel(RowPrep p) {
     const int L = p.seq_len[p.batch_seq[b]];
     const int pos = L + row_index_in_chain(j, p.k);
     if (threadIdx.x == 0) {
-        p.row_tok[t] = j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
+        if (p.tok_matrix) {
+            const int col = min(p.tok_col0 + j, p.tok_len[b] - 1);
+            p.row_tok[t] = p.tok_matrix[(int64_t)b * p.tok_ld + col];
+        } else {
+            p.row_tok[t] = j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
+        }
         p.row_pos[t] = pos;
         p.row_slot[t] = L + j;
     }
@@ -214,6 +219,11 @@ __global__ void add_len_kernel(int32_t* seq_len, const int32_t* batch_seq, int B
     if (b < B) seq_len[batch_seq[b]] += delta;
 }
 
+__global__ void add_len_ragged_kernel(int32_t* seq_len, const int32_t* batch_seq, int B, const int32_t* len, int col0, int width) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) seq_len[batch_seq[b]] += max(0, min(width, len[b] - col0));
+}
+
 // ---------------------------------------------------------------- launchers ---
 
 hipError_t prep_rows(const RowPrep& p, hipStream_t st) {
@@ -288,6 +298,11 @@ hipError_t kv_copy(void* pool, const KvGeom& geom, int layer, const int32_t* pag
 
 hipError_t set_i32(int32_t* p, int32_t v, hipStream_t st) {
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, st, p, v);
+    return hipGetLastError();
+}
+
+hipError_t add_len_ragged(int32_t* seq_len, const int32_t* batch_seq, int B, const int32_t* len, int col0, int width, hipStream_t st) {
+    hipLaunchKernelGGL(add_len_ragged_kernel, dim3((B + 63) / 64), dim3(64), 0, st, seq_len, batch_seq, B, len, col0, width);
     return hipGetLastError();
 }
 

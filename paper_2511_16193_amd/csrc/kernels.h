@@ -31,6 +31,9 @@ struct RowPrep {
     float* rope;                // [T, head_dim/2, 2] cos, sin
     int B, n, k, head_dim;
     float rope_theta;
+    // when set, the tokens come from a matrix of prompts instead: row t = b*n + j holds tok_matrix[b*tok_ld + tok_col0 + j],
+    // or, past the end of prompt b (tok_len[b] tokens), its last token (a padding row whose results are never used)
+    const int32_t* tok_matrix; const int32_t* tok_len; int tok_ld, tok_col0;
 };
 hipError_t prep_rows(const RowPrep& p, hipStream_t st);
 hipError_t embed_rows(const void* embed, int dtype, const int32_t* row_tok, float* h, int T, int d, hipStream_t st);
@@ -56,6 +59,8 @@ hipError_t kv_copy(void* pool, const KvGeom& geom, int layer, const int32_t* pag
                    void* k, void* v, int dtype, bool to_pool, hipStream_t st);
 hipError_t set_i32(int32_t* p, int32_t v, hipStream_t st);
 hipError_t add_len(int32_t* seq_len, const int32_t* batch_seq, int B, int delta, hipStream_t st);
+// seq_len[batch_seq[b]] += min(width, len[b] - col0): what request b really holds of a pass over columns col0 .. col0+width-1
+hipError_t add_len_ragged(int32_t* seq_len, const int32_t* batch_seq, int B, const int32_t* len, int col0, int width, hipStream_t st);
 
 // ---- attention.hip ----
 struct AttnArgs {

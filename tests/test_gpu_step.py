@@ -195,3 +195,60 @@ def test_bf16_prefill_then_step(packed):
     err, exempt, diverged = compare_step(r, g, "bf16", k)
     assert len(diverged) <= 1
     case.close()
+
+
+@pytest.mark.parametrize("k", [4, 8])
+def test_bf16_batched_prefill_of_ragged_prompts(k):
+    """Prompts of 1, 3, 5, 37, 150 and 151 tokens prefetched together through verify_prefill_batch (k + 1 tokens
+    of each per pass; the short ones drop out, the last pass is ragged), handed over in mixed order; last-token
+    logits, lengths and the cache against the oracle's plain causal pass, then one verification step on top."""
+    shape = W.scaled_down(SMALL_BF16, batch=6, k=k)
+    V = shape.vocab
+    lens = [37, 1, 151, 5, 150, 3]
+    B = len(lens)
+    case = Case(shape, [0] * B, verify_mode=OV.STOCHASTIC, synthetic_kv=False, extra_tokens=256, packed=True)
+    prompts = W.make_tokens((B, max(lens)), V, shape.seed + 1, "prompt")
+    lo = np.stack([OV.prefill(case.spec, case.wn, case.caches[b], prompts[b, :lens[b]])[-1] for b in range(B)])
+    ld = case.ver.prefill_batch(list(range(B)), torch.from_numpy(prompts).to(torch.int32), lens).cpu().numpy()
+    assert np.max(np.abs(lo - ld)) < LOGIT_TOL["bf16"]
+    assert np.array_equal(case.device_lengths(), lens)
+    for b in range(B):                       # layer 0 entries: same inputs on both sides
+        kd, vd = case.ver.kv_read(b, 0, 0, lens[b])
+        assert np.mean(kd.float().cpu().numpy() != case.caches[b].k[0][:lens[b]]) < 0.01
+        assert np.mean(vd.float().cpu().numpy() != case.caches[b].v[0][:lens[b]]) < 0.01
+        kd, vd = case.ver.kv_read(b, shape.n_layers - 1, 0, lens[b])
+        assert np.max(np.abs(kd.float().cpu().numpy() - case.caches[b].k[shape.n_layers - 1][:lens[b]])) < 0.03
+    x0 = np.argmax(lo, axis=-1)
+    q = W.make_random_q((B, 1, k), V, 1.0, shape.seed)
+    drafts = W.sample_from(q, shape.seed).numpy()
+    u = W.make_uniforms((B, 1, k + 1), shape.seed)
+    r, g = case.step(x0, drafts, q, u)
+    err, exempt, diverged = compare_step(r, g, "bf16", k)
+    assert len(diverged) <= 1
+    # a second batch of prompts appended to two of the sequences (prefill continues an existing cache)
+    more = W.make_tokens((2, 20), V, shape.seed + 2, "more")
+    for i, b in enumerate((4, 1)):
+        OV.prefill(case.spec, case.wn, case.caches[b], more[i, :20 - 7 * i])
+    before = case.device_lengths()
+    case.ver.prefill_batch([4, 1], torch.from_numpy(more).to(torch.int32), [20, 13], want_logits=False)
+    after = case.device_lengths()
+    assert after[4] == before[4] + 20 and after[1] == before[1] + 13 and np.array_equal(np.delete(after, [1, 4]), np.delete(before, [1, 4]))
+    assert np.array_equal(after, [c.length for c in case.caches])
+    case.close()
+
+
+def test_batched_prefill_refuses_bad_arguments():
+    from paper_2511_16193_amd import SvError
+    import ctypes as C
+    shape = W.scaled_down(SMALL_BF16, batch=2, k=4)
+    case = Case(shape, [0, 0], verify_mode=OV.GREEDY, synthetic_kv=False, packed=True)
+    tok = torch.zeros((2, 8), dtype=torch.int32, device="cuda:0")
+    lib, ctx = case.ver.lib, case.ver.ctx
+    ids, asc, ok = (C.c_int32 * 2)(0, 1), (C.c_int32 * 2)(3, 5), (C.c_int32 * 2)(5, 3)
+    assert lib.verify_prefill_batch(ctx, ids, 2, tok.data_ptr(), 8, asc, None) == -1          # not longest first
+    assert lib.verify_prefill_batch(ctx, ids, 2, tok.data_ptr(), 4, ok, None) == -1           # longer than the pitch
+    assert lib.verify_prefill_batch(ctx, (C.c_int32 * 2)(0, 7), 2, tok.data_ptr(), 8, ok, None) < 0   # no such sequence
+    assert np.array_equal(case.device_lengths(), [0, 0])
+    assert lib.verify_prefill_batch(ctx, ids, 2, tok.data_ptr(), 8, ok, None) == 0
+    assert np.array_equal(case.device_lengths(), [5, 3])
+    case.close()
