@@ -30,6 +30,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the copy-kernel calibration stated there), averaged over the launches of a kind in one step.
+BRACKET_EVERY = 4          # steps of the timed region between two steps whose dominant-kind launches are bracketed by events
+
 MEASURED_TRAFFIC = {
     # profiles/verify_step_cfg2_hbm_traffic.txt: projections (17994 MiB read + 2660 MiB written) / 113 launches;
     # attention main + merge kernel of one layer (602.5 MiB read + 11.6 MiB written)
@@ -206,22 +208,31 @@ def main():
     pre = {name: case.ver.profile_read(kind) for name, kind in kinds.items()}    # (total ms, launches)
     dominant_kind = max(("gemm", "attention", "moe"), key=lambda n: pre[n][0])
 
-    # the timed region: K steps, with event brackets around the launches of the dominant kind only (every
-    # bracket costs a little pipelining between kernels)
+    # the timed region: K steps, with event brackets around the launches of the dominant kind only, and on every
+    # BRACKET_EVERY-th step only (a bracket costs a little pipelining between kernels: ~0.6 ms per step when all
+    # ~110 projection launches of every step are bracketed)
     case.ver.profile_enable(1 << kinds[dominant_kind])
     run(1)
     case.ver.profile_read(kinds[dominant_kind])
+    case.ver.profile_enable(0)
     torch.cuda.synchronize()
+    bracketed_steps = 0
     t0 = time.perf_counter()
-    run(args.steps)
+    for i in range(args.steps):
+        on = i % BRACKET_EVERY == 0
+        if on:
+            case.ver.profile_enable(1 << kinds[dominant_kind])
+            bracketed_steps += 1
+        run(1)
+        if on:
+            case.ver.profile_enable(0)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     timed = case.ver.profile_read(kinds[dominant_kind])
-    case.ver.profile_enable(0)
 
     def per_launch_ms(name):
         tot, n = timed if name == dominant_kind else pre[name]
-        return (tot / n if n else 0.0), (n // (args.steps if name == dominant_kind else pre_steps))
+        return (tot / n if n else 0.0), (n // (bracketed_steps if name == dominant_kind else pre_steps))
 
     gemm_lms, gemm_lps = per_launch_ms("gemm")
     attn_lms, attn_lps = per_launch_ms("attention")
