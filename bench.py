@@ -253,7 +253,7 @@ def main():
         "gemm": {"kernel": "gemm_bf16_ws_kernel (all dense projections + LM head)", "bound": "mfma", "achieved": gemm_tflops,
                  "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
                  "traffic": traffic.get("gemm"), "avg_launch_ms": gemm_lms, "launches_per_step": gemm_lps},
-        "attention": {"kernel": "attn_bf16_kernel + attn_merge_kernel (one layer)", "bound": "hbm", "achieved": attn_gbs,
+        "attention": {"kernel": "attn_bf16_regs_kernel or attn_bf16_kernel + attn_merge_kernel (one layer)", "bound": "hbm", "achieved": attn_gbs,
                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": attn_gbs / PEAK_HBM_GBS,
                       "traffic": traffic.get("attention"), "avg_launch_ms": attn_lms, "launches_per_step": attn_lps},
     }

@@ -14,14 +14,18 @@ namespace sv {
 
 constexpr int NT = 1024;
 
-__global__ __launch_bounds__(NT) void row_stats_kernel(const float* __restrict__ logits, float* __restrict__ stat,
+// One logits row is cut into gridDim.y contiguous parts, one work-group each (a row per work-group leaves a
+// 150k-wide row to 1024 threads and the launch to a few hundred work-groups: latency-bound at a third of the
+// memory rate); part statistics go to `part` [T][parts][4] and row_stats_merge_kernel folds them.
+__global__ __launch_bounds__(NT) void row_stats_kernel(const float* __restrict__ logits, float* __restrict__ part,
                                                        int V, float inv_temp) {
     const int t = blockIdx.x;
     const float* row = logits + (int64_t)t * V;
+    const int span = ((V + gridDim.y - 1) / gridDim.y + 3) & ~3;          // ids per part, a multiple of 4
+    const int vbeg = blockIdx.y * span, vend = min(V, vbeg + span);
     float m = -INFINITY, s = 0.f;
     int am = 0x7fffffff;
-    for (int v = threadIdx.x; v < V; v += NT) {
-        const float x = row[v];
+    auto take = [&](float x, int v) {
         if (x > m) {
             s = s * expf((m - x) * inv_temp) + 1.0f;
             m = x;
@@ -29,6 +33,21 @@ __global__ __launch_bounds__(NT) void row_stats_kernel(const float* __restrict__
         } else if (x > -INFINITY) {
             s += expf((x - m) * inv_temp);
         }
+    };
+    if ((V & 3) == 0) {                                   // rows start on 16-byte boundaries: four ids per load
+        for (int v = vbeg + 4 * threadIdx.x; v < vend; v += 4 * NT) {
+            const floatx4 x = *reinterpret_cast<const floatx4*>(row + v);
+            const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+            if (mx > m) {                                  // new maximum: its first holder among the four
+                s *= expf((m - mx) * inv_temp);            // (m = -inf: s is 0 and stays 0)
+                m = mx;
+                am = x[0] == mx ? v : x[1] == mx ? v + 1 : x[2] == mx ? v + 2 : v + 3;
+            }
+            if (mx > -INFINITY)
+                s += (expf((x[0] - m) * inv_temp) + expf((x[1] - m) * inv_temp)) + (expf((x[2] - m) * inv_temp) + expf((x[3] - m) * inv_temp));
+        }
+    } else {
+        for (int v = vbeg + threadIdx.x; v < vend; v += NT) take(row[v], v);
     }
     __shared__ float sm[NT / 64], ss[NT / 64];
     __shared__ int sa[NT / 64];
@@ -55,11 +74,34 @@ __global__ __launch_bounds__(NT) void row_stats_kernel(const float* __restrict__
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < NT / 64; ++w) merge(m, s, am, sm[w], ss[w], sa[w]);
-        stat[t * 4 + 0] = m;
-        stat[t * 4 + 1] = s;
-        stat[t * 4 + 2] = __int_as_float(am);
-        stat[t * 4 + 3] = 0.f;
+        float* out = part + ((int64_t)t * gridDim.y + blockIdx.y) * 4;
+        out[0] = m;
+        out[1] = s;
+        out[2] = __int_as_float(am);
+        out[3] = 0.f;
     }
+}
+
+__global__ void row_stats_merge_kernel(const float* __restrict__ part, float* __restrict__ stat, int T, int parts, float inv_temp) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    float m = -INFINITY, s = 0.f;
+    int am = 0x7fffffff;
+    for (int i = 0; i < parts; ++i) {                     // ascending ids: on equal maxima the earlier part's id stays
+        const float* in = part + ((int64_t)t * parts + i) * 4;
+        const float m2 = in[0], s2 = in[1];
+        const int a2 = __float_as_int(in[2]);
+        const float mm = fmaxf(m, m2);
+        const float f1 = m == -INFINITY ? 0.f : expf((m - mm) * inv_temp);
+        const float f2 = m2 == -INFINITY ? 0.f : expf((m2 - mm) * inv_temp);
+        s = s * f1 + s2 * f2;
+        if (m2 > m || (m2 == m && a2 < am)) am = a2;
+        m = mm;
+    }
+    stat[t * 4 + 0] = m;
+    stat[t * 4 + 1] = s;
+    stat[t * 4 + 2] = __int_as_float(am);
+    stat[t * 4 + 3] = 0.f;
 }
 
 // Logits row that holds the target distribution of draft slot i (1-based) of chain c of request b.
@@ -304,7 +346,10 @@ __global__ void draw_reduce_kernel(SampleArgs a, int parts) {
 
 hipError_t sample_verify(const SampleArgs& a, hipStream_t st) {
     const int T = a.B * (1 + a.N * a.k), S = a.B * a.N;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(T), dim3(NT), 0, st, a.logits, a.row_stat, a.V, 1.0f / a.temperature);
+    // the race's part buffer is free until the draws: it takes the rows' part statistics first
+    hipLaunchKernelGGL(row_stats_kernel, dim3(T, kDrawParts), dim3(NT), 0, st, a.logits, a.draw_part, a.V, 1.0f / a.temperature);
+    hipLaunchKernelGGL(row_stats_merge_kernel, dim3((T + 63) / 64), dim3(64), 0, st, a.draw_part, a.row_stat, T, kDrawParts,
+                       1.0f / a.temperature);
     if (a.verify_mode == 2) {          // match: the target's token of every slot first, then the comparison
         if (a.sample_mode == 1) {
             hipLaunchKernelGGL(draw_kernel<true>, dim3(T, kDrawParts), dim3(NT), 0, st, a);
