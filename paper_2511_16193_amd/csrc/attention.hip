@@ -659,10 +659,10 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
         wait_vmcnt<0>();                                  // the ring is about to be reused for the merge
     }
 
-    // ---- merge the four waves of the group through LDS (maxima in log2 units from here on) ----
+    // ---- merge the waves of the group through LDS (maxima in log2 units from here on) ----
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) m_run[rt] = m_run[rt] == -INFINITY ? -INFINITY : mc[rt];
-    float (*o_sh)[HD][RP + 1] = reinterpret_cast<float (*)[HD][RP + 1]>(attn_lds);   // [4 waves][HD][RP + 1], over the rings
+    float (*o_sh)[HD][RP + 1] = reinterpret_cast<float (*)[HD][RP + 1]>(attn_lds);   // [W waves][HD][RP + 1], over the rings
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
         float l = l_run[rt];
