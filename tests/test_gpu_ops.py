@@ -107,6 +107,52 @@ def test_attention_bf16_matches_oracle(k, n_chains, group):
     ver.close()
 
 
+@pytest.mark.parametrize("k,n_chains,group,max_tiles", [(4, 1, 7, 4), (8, 3, 5, 4), (8, 3, 5, 3), (8, 1, 7, 2)])
+def test_attention_with_scores_that_keep_growing(k, n_chains, group, max_tiles):
+    """Keys aligned with the queries and growing along the cache, so that the largest score so far rises by
+    some 80 log2 units over each request: the kernels' lazily moved softmax reference has to move several times
+    in mid-stream (in the skewed kernel with PV products of the previous tile still pending), where random keys
+    move it on the first tile only.  Both MFMA kernels (up to 48 stacked rows; more rows / several row groups)."""
+    import paper_2511_16193_amd as P
+    hkv, hd = 2, 128
+    hq = hkv * group
+    n = 1 + n_chains * k
+    lengths = [700, 2047, 3100, 95]
+    B = len(lengths)
+    model = dict(n_layers=1, d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, d_ff=512, vocab=2048,
+                 dtype="bf16", rope_theta=1e6, rms_eps=1e-6)
+    wd = W.make_weights(W.Shape("attn", 1, 256, hq, hkv, hd, 512, 2048), DEV)
+    ver = P.Verifier(model, wd, max_batch=B, max_k=k, max_chains=n_chains, max_seqs=B, page_size=64,
+                     num_pages=B * 52, max_pages_per_seq=51, verify_mode=0)
+    g = torch.Generator().manual_seed(4)
+    u = torch.sign(torch.randn(hd, generator=g))                       # |u|^2 = 128
+    q = (u[None, None, :] * (0.5 + torch.rand((B * n, hq, 1), generator=g)) + 0.3 * torch.randn((B * n, hq, hd), generator=g)).to(torch.bfloat16)
+    ks, vs = [], []
+    for b, L in enumerate(lengths):
+        ver.seq_add(b, L)
+        ramp = torch.linspace(0.0, 5.0, L + n)[:, None, None] * (1.0 if b % 2 == 0 else -1.0) + (0.0 if b % 2 == 0 else 5.0)
+        ks.append((ramp * u[None, None, :] + 0.3 * torch.randn((L + n, hkv, hd), generator=g)).to(torch.bfloat16))
+        vs.append(bf16_cpu((L + n, hkv, hd), 1.0, 50 + b))
+    ids = list(range(B))
+    ver.set_option(P.SV_OPT_ATTN_MAX_ROW_TILES, max_tiles)
+    ver.op_attention(ids, n, k, 0, q.to(DEV))
+    for b in range(B):
+        ver.kv_write(b, 0, 0, ks[b].to(DEV), vs[b].to(DEV))
+    _, _, vis = OV.new_token_layout(k, n_chains)
+    got = ver.op_attention(ids, n, k, 0, q.to(DEV))
+    torch.cuda.synchronize()
+    got = got.float().cpu().numpy().reshape(B, n, hq, hd)
+    for b, L in enumerate(lengths):
+        mask = np.concatenate([np.ones((n, L), dtype=bool), vis], axis=1)
+        qb = q[b * n:(b + 1) * n].double().numpy()
+        want = M.attend(qb, ks[b].double().numpy(), vs[b].double().numpy(), mask)
+        spread = M.attend(qb, ks[b].double().numpy(), np.abs(vs[b].double().numpy()), mask)
+        tol = 2.0 ** -8 * (np.abs(want) + spread) + 1e-6
+        assert np.all(np.isfinite(got[b]))
+        assert np.all(np.abs(got[b] - want) <= tol), (b, L, float(np.max(np.abs(got[b] - want))))
+    ver.close()
+
+
 def random_case(B, N, k, V, seed, sigma_q=1.0, with_q=True):
     rng = np.random.default_rng(seed)
     logits = (rng.standard_normal((B, 1 + N * k, V)) * 1.2).astype(np.float32)
