@@ -124,6 +124,9 @@ def main():
     ap.add_argument("--verify", choices=["config", "greedy", "stochastic", "match"], default="config",
                     help="verification rule (default: the configuration's); with `match` the synthetic drafts are "
                          "rarely accepted: use it to time the rule, not for the headline figure")
+    ap.add_argument("--drop-row-major", action="store_true",
+                    help="free the row-major copy of the weights once they are packed (no oracle baseline then); "
+                         "needed for cfg5 at its full batch")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps run one plain elementwise pass that reads 1 GiB and writes 1 GiB "
                          "(torch.neg(src, out=dst) on fp32, an op nothing else in the run uses), the known-size kernel against which the HBM byte "
@@ -148,7 +151,9 @@ def main():
     if args.batch is not None:
         shape = W.scaled_down(shape, batch=args.batch)
     vmode = {"config": None, "greedy": 0, "stochastic": 1, "match": 2}[args.verify]
-    case = DeviceCase(shape, k=args.k, verify_mode=vmode, log=log)
+    if args.drop_row_major:
+        args.cpu_seqs = 0
+    case = DeviceCase(shape, k=args.k, verify_mode=vmode, keep_row_major=not args.drop_row_major, log=log)
     if args.gemm_variant is not None:
         case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
     if args.attn_chunk is not None:

@@ -21,7 +21,8 @@ from . import synth
 
 class DeviceCase:
     def __init__(self, shape: Shape, *, k: int | None = None, n_chains: int | None = None, page_size: int = 64,
-                 verify_mode: int | None = None, sample_mode: int = 1, packed: bool = True, device="cuda:0", log=None):
+                 verify_mode: int | None = None, sample_mode: int = 1, packed: bool = True, keep_row_major=True,
+                 device="cuda:0", log=None):
         from paper_2511_16193_amd import Verifier, pack_weights
         self.shape, self.device = shape, torch.device(device)
         self.k = shape.k if k is None else k
@@ -36,7 +37,16 @@ class DeviceCase:
         self.weights = synth.make_weights(shape, self.device)           # row-major (what the oracle reads)
         # the library streams the projection matrices in its packed order (a one-off device-side reorder)
         self.weights_dev = pack_weights(self.weights) if packed and shape.dtype == "bf16" else self.weights
-        self.ver = Verifier(shape.model_fields(), self.weights_dev, packed=self.weights_dev is not self.weights,
+        packed_now = self.weights_dev is not self.weights
+        if packed_now and keep_row_major == "host":       # the largest configurations have no room for both copies on
+            cpu = {k: v.cpu() for k, v in self.weights.items() if k != "layers"}     # the device: the oracle's goes to the host
+            cpu["layers"] = [{k: v.cpu() for k, v in lw.items()} for lw in self.weights["layers"]]
+            self.weights = cpu
+            torch.cuda.empty_cache()
+        elif packed_now and not keep_row_major:
+            self.weights = None
+            torch.cuda.empty_cache()
+        self.ver = Verifier(shape.model_fields(), self.weights_dev, packed=packed_now,
                             max_batch=self.B, max_k=max(self.k, 1),
                             max_chains=self.N, max_seqs=self.B, page_size=page_size, num_pages=sum(pages) + 4,
                             max_pages_per_seq=max(pages) + 1,
