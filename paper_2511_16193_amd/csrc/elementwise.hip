@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
                     const int i = threadIdx.x + v * 256;
-                    y[u][v] = (i < nq) & (j0 + u < top_k) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+                    y[u][v] = ((i < nq) & (j0 + u < top_k)) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
                 }
             }
 #pragma unroll
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
                     const int i = threadIdx.x + v * 256;
-                    y[u][v] = (i < nq) & (s0 + u < S) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
+                    y[u][v] = ((i < nq) & (s0 + u < S)) ? pr[i] : floatx4{0.f, 0.f, 0.f, 0.f};
                 }
             }
 #pragma unroll
