@@ -508,7 +508,7 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
             double best = 1e300;
             std::vector<int> lens;
             std::vector<double> cu(256);
-            for (int cand : {1024, 1536, 2048, 3072, 4096, 6144, 8192}) {
+            for (int cand : {1024, 1536, 2048, 3072, 4096, 6144, 8192, 12288, 16384, 24576, 32768}) {
                 lens.clear();
                 for (int b = 0; b < B; ++b) {
                     const int total = c->seqs[ids[b]].len_ub + extra;
