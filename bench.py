@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector ALUs
 
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the copy-kernel calibration stated there), averaged over the launches of a kind in one step.
@@ -61,8 +62,9 @@ def moe_bytes_per_layer(s, T):
 
 
 def attention_bytes_per_layer(s, lengths, n):
-    kv_row = 2 * s.n_kv_heads * s.head_dim * 2                      # K and V of one token in one layer, bf16
-    q_o = 2 * len(lengths) * n * s.n_q_heads * s.head_dim * 2       # Q read + output written
+    es = 4 if s.dtype == "fp32" else 2                              # bytes per cached element
+    kv_row = 2 * s.n_kv_heads * s.head_dim * es                     # K and V of one token in one layer
+    q_o = 2 * len(lengths) * n * s.n_q_heads * s.head_dim * es      # Q read + output written
     return float(sum(int(L) + n for L in lengths)) * kv_row + q_o
 
 
@@ -254,11 +256,14 @@ def main():
     gemm_tflops = flops / gemm_launches / (gemm_lms * 1e-3) / 1e12
     attn_gbs = abytes / (attn_lms * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get(shape.name if args.batch is None and args.k is None else "", {})
+    fp32 = shape.dtype == "fp32"     # fp32 models: plain-ALU projections (fp32 vector peak) and the generic attention kernel
+    gemm_peak = PEAK_FP32_TFLOPS if fp32 else PEAK_BF16_TFLOPS
     roofs = {
-        "gemm": {"kernel": "gemm_bf16_ws_kernel (all dense projections + LM head)", "bound": "mfma", "achieved": gemm_tflops,
-                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
+        "gemm": {"kernel": "gemm_f32_kernel (all dense projections + LM head)" if fp32 else "gemm_bf16_ws_kernel (all dense projections + LM head)",
+                 "bound": "alu" if fp32 else "mfma", "achieved": gemm_tflops,
+                 "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops / gemm_peak,
                  "traffic": traffic.get("gemm"), "avg_launch_ms": gemm_lms, "launches_per_step": gemm_lps},
-        "attention": {"kernel": "attn_bf16_regs_kernel or attn_bf16_kernel + attn_merge_kernel (one layer)", "bound": "hbm", "achieved": attn_gbs,
+        "attention": {"kernel": "attn_generic_kernel (one layer)" if fp32 else "attn_bf16_regs_kernel or attn_bf16_kernel + attn_merge_kernel (one layer)", "bound": "hbm", "achieved": attn_gbs,
                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": attn_gbs / PEAK_HBM_GBS,
                       "traffic": traffic.get("attention"), "avg_launch_ms": attn_lms, "launches_per_step": attn_lps},
     }
