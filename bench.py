@@ -183,11 +183,19 @@ def main():
     log(f"warm-up {args.warmup} steps ...")
     run(args.warmup)
     torch.cuda.synchronize()
-    # un-instrumented pass, for reference in the log
+    # un-instrumented pass, for reference in the log; an event between steps (on the stream the library launches
+    # on, torch's current one) gives the spread of the single steps
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    run(args.steps)
+    for i in range(args.steps):
+        marks[i].record()
+        run(1)
+    marks[args.steps].record()
     torch.cuda.synchronize()
     plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    each = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    pick = lambda f: each[min(len(each) - 1, int(round(f * (len(each) - 1))))]
+    step_spread = {"p10": pick(0.1), "p50": pick(0.5), "p90": pick(0.9)} if each else None
 
     # the same steps replayed from a HIP graph (reported beside the contract's figure: the event brackets of the
     # timed region below cannot be recorded inside a graph)
@@ -303,6 +311,7 @@ def main():
         "accepted_drafts_tokens_per_s": int(acc.sum()) / (ms_per_step * 1e-3),
         "roofline": dominant, "roofline_other": other,
         "sampler_ms_per_step": samp_ms, "ms_per_step_without_event_brackets": plain_ms,
+        "step_ms_without_event_brackets": step_spread,
         "ms_per_step_graph_replay": graph_ms,
         "cpu_baseline": cpu,
     }
