@@ -508,17 +508,20 @@ __global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_w
     gemm_bf16_ws_body<MT, NT, KA, PD, GLU>(Ap, Wp, out, M, N, K, k_per_split, splits, tiles_m, tiles_n, tn0, blockIdx.x);
 }
 
-// Gate/up projection with a short last round: the first n_main work-groups are 160-row ones over the strips
-// [0, strips_main); the rest are 32-row ones over the remaining strips.  One launch: the small work-groups
-// start on whichever CUs free up first instead of waiting for the whole main round.
+// Gate/up projection with a short last round: the first n_main work-groups are 160-row ones over the 128-feature
+// strips [0, strips_main); the rest are 64-row ones over the remaining strips cut in two (64 features each).  One
+// launch: the small work-groups start on whichever CUs free up first instead of waiting for the whole main round.
+// A small work-group streams the whole reduction depth of its weight rows whatever its share of the products,
+// so the last round is bound by how often the strips are re-read from L2: 64 rows x 64 features (five readers of
+// 0.9 MB per half strip) take 26 us where 32 rows x 128 features (ten readers of 1.8 MB) took 35 us.
 __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_glu_mixed_kernel(
     const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out, int M, int N, int K,
-    int tiles_m, int strips_main, int tiles_m1, int strips_tail) {
+    int tiles_m, int strips_main, int tiles_m2, int strips_tail) {
     const int n_main = tiles_m * strips_main;
     if ((int)blockIdx.x < n_main)
         gemm_bf16_ws_body<5, 2, 8, 8, true>(Ap, Wp, out, M, N, K, K, 1, tiles_m, strips_main, 0, blockIdx.x);
     else
-        gemm_bf16_ws_body<1, 2, 8, 8, true>(Ap, Wp, out, M, N, K, K, 1, tiles_m1, strips_tail, strips_main, blockIdx.x - n_main);
+        gemm_bf16_ws_body<2, 1, 8, 8, true>(Ap, Wp, out, M, N, K, K, 1, tiles_m2, 2 * strips_tail, 2 * strips_main, blockIdx.x - n_main);
 }
 
 // Activations [M, K] row-major -> packed [ceil(M/32)][K/16][64 lanes][8]: lane 32*g + r of a fragment holds
@@ -560,8 +563,8 @@ hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out,
     if (F % 128 == 0 && K % 128 == 0) {
         // 128-feature strips, gate and up in one wave.  One work-group per CU: the launch runs in rounds of 256,
         // and a last round that is less than half full would leave most CUs idle for a whole work-group's time.
-        // Its strips are then given to 32-row work-groups (five times as many, a fifth as long) at the end of the
-        // same launch.
+        // Its strips are then given to 64-row work-groups of half a strip each (five times as many, a fifth of the
+        // products) at the end of the same launch.
         const int mt = gemm_bf16_ws_row_tiles(M);
         const int tiles_m = (M + 32 * mt - 1) / (32 * mt), strips = F / 128;
         const int rem = (strips * tiles_m) % 256;
@@ -582,9 +585,11 @@ hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out,
         } else if (strips_main == 0)
             hipLaunchKernelGGL((gemm_bf16_ws_kernel<1, 2, 8, 8, true>), dim3(tiles_m1 * strips_tail), dim3(256), 0, st, Ap, Wp,
                                out, M, 2 * F, K, K, 1, tiles_m1, strips_tail, 0);
-        else
-            hipLaunchKernelGGL(gemm_bf16_ws_glu_mixed_kernel, dim3(tiles_m * strips_main + tiles_m1 * strips_tail), dim3(256), 0,
-                               st, Ap, Wp, out, M, 2 * F, K, tiles_m, strips_main, tiles_m1, strips_tail);
+        else {
+            const int tiles_m2 = (M + 63) / 64;
+            hipLaunchKernelGGL(gemm_bf16_ws_glu_mixed_kernel, dim3(tiles_m * strips_main + tiles_m2 * 2 * strips_tail), dim3(256), 0,
+                               st, Ap, Wp, out, M, 2 * F, K, tiles_m, strips_main, tiles_m2, strips_tail);
+        }
         return hipGetLastError();
     }
     const int tiles_m = (M + 159) / 160, tiles_n = F / 64;
