@@ -36,7 +36,7 @@ BRACKET_EVERY = 4          # steps of the timed region between two steps whose d
 MEASURED_TRAFFIC = {
     # profiles/verify_step_cfg2_hbm_traffic.txt: projections (17994 MiB read + 2660 MiB written) / 113 launches;
     # attention main + merge kernel of one layer (602.5 MiB read + 11.6 MiB written)
-    "cfg2-7b-b64-k4": {"gemm": 191.7e6, "attention": 643.9e6},
+    "cfg2-7b-b64-k4": {"gemm": 189.9e6, "attention": 643.9e6},
     # profiles/verify_step_cfg4_hbm_traffic.txt: expert FFN kernels of one layer (1404.9 MiB read + 77.1 MiB
     # written); attention main + merge kernel of one layer (1227.1 MiB read + 20.2 MiB written)
     "cfg4-moe-b128-k4": {"moe": 1554.0e6, "attention": 1307.9e6},
