@@ -171,6 +171,31 @@ def test_small_bf16_step_with_synthetic_cache(k, n_chains, vmode, smode, packed)
     case.close()
 
 
+WIDE_FFN = W.Shape("wide-ffn-bf16", 1, 256, 8, 2, 128, 33792, 2048, dtype="bf16", batch=32, k=4, seed=91)
+
+
+def test_bf16_wide_ffn_gate_up_launch_with_a_short_last_round():
+    """One layer whose FFN is 33792 wide under 160 rows (32 requests, k = 4): 264 strips of 128 features for one
+    160-row tile, i.e. one full round of 256 work-groups and a last round of 8 strips, which the fused gate/up
+    projection hands to 64-row work-groups of half a strip in the same launch.  Logits and decisions against the
+    oracle; the down projection that follows reads every feature, so a strip left out or written twice shows."""
+    shape = WIDE_FFN
+    B, V, k = shape.batch, shape.vocab, shape.k
+    lengths = [5 + 7 * b for b in range(B)]
+    case = Case(shape, lengths, verify_mode=OV.STOCHASTIC, sample_mode=OV.SAMPLE_EXP_RACE, packed=True)
+    x0 = W.make_tokens((B,), V, shape.seed, "x0")
+    q = W.make_random_q((B, 1, k), V, 1.0, shape.seed)
+    drafts = W.sample_from(q, shape.seed).numpy()
+    u = W.make_uniforms((B, 1, k + 1), shape.seed)
+    r, g = case.step(x0, drafts, q, u)
+    err, exempt, diverged = compare_step(r, g, "bf16", k)
+    assert err < LOGIT_TOL["bf16"]
+    assert len(diverged) <= 1
+    keep = np.array([b not in diverged for b in range(B)])
+    assert np.array_equal(case.device_lengths()[keep], np.array([c.length for c in case.caches])[keep])
+    case.close()
+
+
 @pytest.mark.parametrize("packed", [False, True])
 def test_bf16_prefill_then_step(packed):
     """Real prefill on both sides (no synthetic cache): prompts of 150 tokens run through verify_prefill in chunks,
