@@ -102,7 +102,7 @@ struct MoeArgs {
     int32_t* perm;            // [32 * max_tiles] source row of a padded row
     int32_t* inv;             // [T * top_k] padded row of an assignment
     bf16_t* act;              // [max_tiles][F/16][64][8] SwiGLU outputs as operand tiles
-    float* y;                 // [32 * max_tiles][d] expert outputs
+    float* y;                 // [32 * max_tiles][d] expert outputs (until the first product has read them: the buckets' rows as bf16 operand tiles)
     float* out;               // [T][d] combined result
     int T, d, E, top_k, F;
 };
