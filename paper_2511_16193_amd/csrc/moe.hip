@@ -237,7 +237,10 @@ __global__ __launch_bounds__(256, 2) void moe_gemm_kernel(MoeArgs a) {
     const int K = MODE == 0 ? a.d : a.F;                    // reduction width
     const int Ntot = MODE == 0 ? 2 * a.F : a.d;             // weight rows per expert
     const int strips = MODE == 0 ? a.F / 64 : a.d / 128;
-    const int e = blockIdx.x / strips, p = blockIdx.x % strips;
+    // consecutive work-group ids go round the eight XCDs: the strips of an expert are given ids eight apart, so
+    // that they share one L2 and the expert's tiles are fetched once (E is a multiple of 8)
+    const int grp = blockIdx.x / (8 * strips), in_grp = blockIdx.x % (8 * strips);
+    const int e = grp * 8 + (in_grp & 7), p = in_grp >> 3;
     const int tile0 = a.tile_off[e], ntile = a.tile_off[e + 1] - tile0;
     if (ntile == 0) return;
     const int kslices = K / 16, nfill = kslices / KA;
