@@ -24,7 +24,7 @@ def noisy_greedy_drafts(case, b, x0, k, sigma, rng):
 
 
 def test_cfg1_tiny_fp32_greedy_chained_steps():
-    """BASELINE configuration 1 in full: 2 layers, d 256, 4 heads x 64, vocab 2048, fp32; B=4 prompts of 128
+    """Workload configuration 1 (cfg1) in full: 2 layers, d 256, 4 heads x 64, vocab 2048, fp32; B=4 prompts of 128
     random ids; real prefill on both sides; k=4 drafts = argmax(target logits + noise) produced one token at
     a time by the oracle; greedy verification; 8 chained steps so that rollback is exercised.  Tokens and
     accepted lengths must be identical, logits within 1e-4, cache contents within 1e-4 after every step."""
