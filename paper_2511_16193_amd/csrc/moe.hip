@@ -174,13 +174,26 @@ __global__ __launch_bounds__(1024) void moe_group_kernel(MoeArgs a) {
         cnts[e] = run;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int tiles = 0;
-        for (int e = 0; e < a.E; ++e) {
-            offs[e] = tiles;
-            tiles += (cnts[e] + 31) / 32;
+    // first tile of every bucket: exclusive prefix sum of the buckets' tile counts (E <= 256: four waves scan
+    // their 64 experts with lane shifts, then add the totals of the waves before them)
+    {
+        __shared__ int wave_tot[4];
+        const int e = threadIdx.x, lane = e & 63;
+        const int mine = e < a.E ? (cnts[e] + 31) / 32 : 0;
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
         }
-        offs[a.E] = tiles;
+        if (e < 256 && lane == 63) wave_tot[e >> 6] = incl;
+        __syncthreads();
+        if (e < 256) {
+            int base = 0;
+            for (int w = 0; w < (e >> 6); ++w) base += wave_tot[w];
+            if (e < a.E) offs[e] = base + incl - mine;
+            if (e == a.E - 1) offs[a.E] = base + incl;
+        }
     }
     __syncthreads();
     for (int e = threadIdx.x; e <= a.E; e += 1024) {
