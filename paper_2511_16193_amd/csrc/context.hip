@@ -606,7 +606,7 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
     rp.last_tokens = last_tokens; rp.drafts = drafts;
     rp.row_tok = c->at<int32_t>(L.row_tok); rp.row_pos = c->at<int32_t>(L.row_pos); rp.row_slot = c->at<int32_t>(L.row_slot);
     rp.rope = c->at<float>(L.rope);
-    rp.B = B; rp.n = n; rp.k = k; rp.head_dim = m.head_dim; rp.rope_theta = m.rope_theta;
+    rp.B = B; rp.n = n; rp.k = k; rp.head_dim = m.head_dim; rp.vocab = m.vocab; rp.rope_theta = m.rope_theta;
     rp.tok_matrix = c->tok_matrix; rp.tok_len = c->tok_len; rp.tok_ld = c->tok_ld; rp.tok_col0 = c->tok_col0;
     SV_HIP(c, prep_rows(rp, st));
     SV_HIP(c, embed_rows(c->embed, m.dtype, rp.row_tok, h, T, d, st));
@@ -799,6 +799,9 @@ static int step_device_work(sv_ctx* c, const sv_batch* bt, const int32_t* drafts
 }
 
 static void drop_graphs(sv_ctx* c) {
+    bool launched = false;
+    for (auto& g : c->graphs) launched |= g.exec != nullptr;
+    if (launched) (void)hipStreamSynchronize(c->stream);  // an executable graph may still be replaying on the stream
     for (auto& g : c->graphs)
         if (g.exec) (void)hipGraphExecDestroy(g.exec);
     c->graphs.clear();
@@ -823,7 +826,10 @@ static int step_through_graph(sv_ctx* c, const sv_batch* bt, const int32_t* draf
             size_t old = 0;
             for (size_t i = 1; i < c->graphs.size(); ++i)
                 if (c->graphs[i].used < c->graphs[old].used) old = i;
-            if (c->graphs[old].exec) (void)hipGraphExecDestroy(c->graphs[old].exec);
+            if (c->graphs[old].exec) {
+                (void)hipStreamSynchronize(c->stream);     // it may still be replaying
+                (void)hipGraphExecDestroy(c->graphs[old].exec);
+            }
             c->graphs.erase(c->graphs.begin() + old);
         }
         sv_ctx::GraphEntry g;

@@ -14,12 +14,16 @@ __global__ void prep_rows_kernel(RowPrep p) {
     const int L = p.seq_len[p.batch_seq[b]];
     const int pos = L + row_index_in_chain(j, p.k);
     if (threadIdx.x == 0) {
+        int tok;
         if (p.tok_matrix) {
             const int col = min(p.tok_col0 + j, p.tok_len[b] - 1);
-            p.row_tok[t] = p.tok_matrix[(int64_t)b * p.tok_ld + col];
+            tok = p.tok_matrix[(int64_t)b * p.tok_ld + col];
         } else {
-            p.row_tok[t] = j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
+            tok = j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
         }
+        // ids arrive in device memory from another process and cannot be checked on the host: an id outside the
+        // vocabulary is embedded as the nearest valid one (the sampler rejects such a draft whatever its row yields)
+        p.row_tok[t] = min(max(tok, 0), p.vocab - 1);
         p.row_pos[t] = pos;
         p.row_slot[t] = L + j;
     }

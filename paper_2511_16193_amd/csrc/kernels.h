@@ -29,7 +29,7 @@ struct RowPrep {
     int32_t* row_pos;           // [T]
     int32_t* row_slot;          // [T]
     float* rope;                // [T, head_dim/2, 2] cos, sin
-    int B, n, k, head_dim;
+    int B, n, k, head_dim, vocab;
     float rope_theta;
     // when set, the tokens come from a matrix of prompts instead: row t = b*n + j holds tok_matrix[b*tok_ld + tok_col0 + j],
     // or, past the end of prompt b (tok_len[b] tokens), its last token (a padding row whose results are never used)

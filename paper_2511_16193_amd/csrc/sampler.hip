@@ -121,7 +121,9 @@ __global__ void accept_kernel(SampleArgs a) {
         const int row = slot_row(b, c, i, n, a.k);
         const int x = a.drafts[(int64_t)s * a.k + (i - 1)];
         bool ok;
-        if (a.verify_mode == 0) {
+        if ((unsigned)x >= (unsigned)a.V) {
+            ok = false;                                   // not a token of this vocabulary: rejected, nothing is read at it
+        } else if (a.verify_mode == 0) {
             ok = x == __float_as_int(a.row_stat[row * 4 + 2]);
         } else if (a.verify_mode == 2) {
             ok = x == __float_as_int(a.row_stat[row * 4 + 3]);       // the token drawn for this slot
@@ -162,8 +164,10 @@ __global__ __launch_bounds__(NT) void draw_kernel(SampleArgs a) {
     const bool rejected = ROWS ? false : acc < klim;
     const int row = ROWS ? s : a.chain_row[s];
     const float* lrow = a.logits + (int64_t)row * a.V;
-    const float* qrow = (rejected && a.draft_probs) ? a.draft_probs + ((int64_t)s * a.k + acc) * a.V : nullptr;
-    const int xrej = rejected ? a.drafts[(int64_t)s * a.k + acc] : -1;
+    // a rejected id outside the vocabulary was rejected unread: the replacement comes from p_r itself (q taken as zero)
+    const int xraw = rejected ? a.drafts[(int64_t)s * a.k + acc] : -1;
+    const int xrej = (unsigned)xraw < (unsigned)a.V ? xraw : -1;
+    const float* qrow = (rejected && a.draft_probs && xrej >= 0) ? a.draft_probs + ((int64_t)s * a.k + acc) * a.V : nullptr;
     const float inv_temp = 1.0f / a.temperature;
     const float m = a.row_stat[row * 4], sum = a.row_stat[row * 4 + 1];
     const float log_sum = logf(sum);

@@ -214,6 +214,8 @@ CASES = [
     (4, 1, 0, 2048, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, False, False),       # k = 0: plain decoding
     (16, 1, 4, 152064, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, True, False),     # full vocabulary
     (8, 1, 4, 152064, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, 1.0, True, False),
+    (16, 1, 4, 152064, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, False, False),    # one-hot drafts at the full vocabulary
+    (12, 3, 8, 152064, OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, 1.0, False, True),     # the same with three chains, ragged windows
     (1, 1, 1, 16, OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, 1.0, True, False),       # degenerate sizes
 ]
 
@@ -305,3 +307,39 @@ def test_sampler_zero_residual_falls_back_to_target():
                                 verify_mode=OV.STOCHASTIC, sample_mode=smode)
         torch.cuda.synchronize()
         assert int(ga[0]) == 0 and int(gout[0, 0]) == 7
+
+
+@pytest.mark.parametrize("vmode,smode,with_q", [(OV.GREEDY, 0, False), (OV.STOCHASTIC, OV.SAMPLE_EXP_RACE, True),
+                                                (OV.STOCHASTIC, OV.SAMPLE_INVERSE_CDF, False), (OV.MATCH, OV.SAMPLE_EXP_RACE, False)])
+def test_sampler_rejects_draft_ids_outside_the_vocabulary(vmode, smode, with_q):
+    """Draft ids arrive in device memory from the drafter's process and cannot be checked on the host.  An id
+    below 0 or >= vocab is rejected without being used as an index, and the token supplied for its slot is drawn
+    from the target's distribution of that slot (q taken as zero): exactly what a draft window that ends just
+    before that slot gives, which is how the oracle states the expectation."""
+    from paper_2511_16193_amd import op_sample
+    B, N, k, V = 8, 1, 4, 2048
+    logits, drafts, q, u = random_case(B, N, k, V, 77, with_q=with_q)
+    # make every draft acceptable up to the planted slot: greedy / match need the target's own token there
+    if vmode == OV.GREEDY:
+        drafts[:, 0] = np.argmax(logits[:, :k], axis=-1)
+    if vmode == OV.MATCH:
+        p = M.softmax(logits.astype(np.float64), axis=-1).reshape(B * (k + 1), V)
+        t, _ = OV.draw_exp_race(p, u[:, 0, :].reshape(-1).astype(np.float32), np.repeat(np.arange(B, dtype=np.uint64), k + 1))
+        drafts[:, 0] = t.reshape(B, k + 1)[:, :k]
+    bad_slot = np.array([0, 1, 2, 3, 0, 1, 2, 3])                 # 0-based slot of the planted id
+    bad_id = np.array([-1, V, V + 12345, -2**31, 2**31 - 1, -5, V, V + 1])
+    planted = drafts.copy()
+    planted[np.arange(B), 0, bad_slot] = bad_id
+    a, out, best, margin = oracle_sample(logits, drafts, q, u, vmode, smode, 1.0, bad_slot.copy())
+    ga, gout, gbest = op_sample(
+        torch.from_numpy(logits).to(DEV), torch.from_numpy(planted).to(torch.int32).to(DEV).contiguous(),
+        None if q is None else q.to(DEV).contiguous(), torch.from_numpy(u).to(DEV),
+        verify_mode=vmode, sample_mode=smode, temperature=1.0)
+    torch.cuda.synchronize()
+    ga, gout = ga.cpu().numpy(), gout.cpu().numpy()
+    assert np.all(ga <= bad_slot)                                 # never past the planted id
+    for b in range(B):
+        assert 0 <= gout[b, ga[b]] < V                            # the supplied token is a valid one
+        if margin[b] >= 1e-5:
+            assert ga[b] == a[b] and np.array_equal(gout[b], out[b]), (b, ga[b], a[b], gout[b], out[b])
+    assert (a == bad_slot).sum() >= 2                             # some walks did reach the planted id
