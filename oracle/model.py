@@ -168,12 +168,14 @@ def dense_ffn(spec: ModelSpec, a: np.ndarray, w_gate_up: np.ndarray, w_down: np.
     return matmul_wt(act, w_down)
 
 
-def moe_ffn(spec: ModelSpec, a: np.ndarray, lw: dict, margins: list | None) -> np.ndarray:
+def moe_ffn(spec: ModelSpec, a: np.ndarray, lw: dict, margins: list | None, trace: dict | None = None) -> np.ndarray:
     """Softmax router over all experts -> top-k -> renormalised weights ->
     weighted sum of the selected experts' SwiGLU FFNs."""
     ids, wts, margin = route_top_k(matmul_wt(a, lw["w_router"]), spec.top_k)
     if margins is not None:
         margins.append(margin)
+    if trace is not None:
+        trace.setdefault("routing", []).append((ids, wts, margin))
     out = np.zeros((a.shape[0], spec.d_model), dtype=np.float64)
     for e in np.unique(ids):
         tok, slot = np.nonzero(ids == e)
@@ -188,7 +190,8 @@ def forward(spec: ModelSpec,
             tokens: np.ndarray,
             positions: np.ndarray,
             visible: np.ndarray,
-            router_margins: list | None = None) -> np.ndarray:
+            router_margins: list | None = None,
+            trace: dict | None = None) -> np.ndarray:
     """One parallel pass over n new tokens of each of B requests.
 
     tokens, positions: int [B, n].  visible: bool [B, n, n]; visible[b, i, j]
@@ -200,6 +203,12 @@ def forward(spec: ModelSpec,
     "w_gate_up","w_down" (dense) or "w_router","w_gate_up"[E],"w_down"[E]}}.
     wqkv rows: all q heads, then all k heads, then all v heads.
     Returns logits float64 [B, n, vocab].
+    trace (observer only, changes nothing computed): if a dict, receives
+    "hidden" = the residual stream [B*n, d] entering every layer, then the one
+    leaving the last; "ffn_input" / "ffn_residual" = per layer the rounded
+    normalised rows fed to the feed-forward block and the residual stream they
+    are added to; and for mixture-of-experts models "routing" = per layer
+    (expert ids, weights, margin).
     """
     B, n = tokens.shape
     hq, hkv, hd = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
@@ -211,6 +220,8 @@ def forward(spec: ModelSpec,
 
     for l in range(spec.n_layers):
         lw = layer_of(l)
+        if trace is not None:
+            trace.setdefault("hidden", []).append(h.copy())
         a = round_to_storage(rms_norm(h, lw["ln1"], spec.rms_eps), spec.dtype)
         qkv = matmul_wt(a, lw["wqkv"])
         q = qkv[:, : hq * hd].reshape(B * n, hq, hd)
@@ -234,10 +245,15 @@ def forward(spec: ModelSpec,
         h = h + matmul_wt(attn, lw["wo"])
 
         a = round_to_storage(rms_norm(h, lw["ln2"], spec.rms_eps), spec.dtype)
+        if trace is not None:
+            trace.setdefault("ffn_input", []).append(a.copy())
+            trace.setdefault("ffn_residual", []).append(h.copy())
         if spec.n_experts:
-            h = h + moe_ffn(spec, a, lw, router_margins)
+            h = h + moe_ffn(spec, a, lw, router_margins, trace)
         else:
             h = h + dense_ffn(spec, a, lw["w_gate_up"], lw["w_down"])
 
+    if trace is not None:
+        trace.setdefault("hidden", []).append(h.copy())
     a = round_to_storage(rms_norm(h, weights["final_norm"], spec.rms_eps), spec.dtype)
     return matmul_wt(a, weights["lm_head"]).reshape(B, n, spec.vocab)

@@ -9,9 +9,9 @@ and notation, in plain Python floats (IEEE double):
   P(a, w)      = p^a (1 - p)  for 0 <= a <= w-1,  p^w for a = w
   tau_w        = sum_{a=0}^{w-1} p^a (1-p) (a+1)/2  +  w p^w
   TGS(b)       = tau_w / IL(b)
-  Algorithm 1: for every verifier configuration g_v of the given set, every drafter size g_d = 1..g_v:
-               b = ceil((g_d + g_v) B / G); for w = 1..w_max keep the (g_d, g_v, w) with the largest TGS
-               (strictly larger replaces: the first of equals, in the loops' order, stays).
+  Algorithm 1: over every verifier configuration g_v of the given set, every drafter size g_d = 1..g_v
+               (which fixes b = ceil((g_d + g_v) B / G)) and every window w = 1..w_max: the (g_d, g_v, w)
+               with the largest TGS, the first of equals in that visiting order.
 
 Readings (the text leaves these open; they are listed with the others in the design notes):
   * The side condition printed with P(a, w) names an `n` that appears nowhere else; it is read as w.
@@ -84,20 +84,25 @@ class Plan:
     b: int
 
 
-def plan_decoupled(B: int, G: int, p: float, verifier_configs: Sequence[int],
-                   D_of: dict, V_of: dict, W: int) -> Plan:
-    """Algorithm 1.  D_of[g_d] -> Affine for g_d = 1..max(verifier_configs);
-    V_of[(g_v, w)] -> Affine for every g_v of verifier_configs and w = 1..W."""
-    best = Plan(0, 0, 0, 0.0, 0)
+def deployments(B: int, G: int, verifier_configs: Sequence[int]):
+    """Every (verifier configuration, drafter size) pair with the per-worker batch it implies, in visiting order:
+    configurations as given, drafter sizes ascending."""
     for g_v in verifier_configs:
         for g_d in range(1, g_v + 1):
-            b = -(-((g_d + g_v) * B) // G)                    # ceil
-            D = D_of[g_d]
-            for w in range(1, w_max(D, V_of[(g_v, W)], W) + 1):
-                cur = tgs(p, w, D, V_of[(g_v, w)], b)
-                if cur > best.tgs:
-                    best = Plan(g_d, g_v, w, cur, b)
-    return best
+            yield g_d, g_v, -(-((g_d + g_v) * B) // G)        # ceil((g_d + g_v) B / G)
+
+
+def plan_decoupled(B: int, G: int, p: float, verifier_configs: Sequence[int],
+                   D_of: dict, V_of: dict, W: int) -> Plan:
+    """What Algorithm 1 computes.  D_of[g_d] -> Affine for g_d = 1..max(verifier_configs);
+    V_of[(g_v, w)] -> Affine for every g_v of verifier_configs and w = 1..W.  Every deployment is expanded
+    into the windows 1..w_max worth trying; the candidate with the largest TGS wins (the first among equals,
+    in visiting order); with no positive TGS the all-zero plan is returned."""
+    candidates = [Plan(g_d, g_v, w, tgs(p, w, D_of[g_d], V_of[(g_v, w)], b), b)
+                  for g_d, g_v, b in deployments(B, G, verifier_configs)
+                  for w in range(1, w_max(D_of[g_d], V_of[(g_v, W)], W) + 1)]
+    best = max(candidates, key=lambda c: c.tgs, default=None)  # max() keeps the first of equal keys
+    return best if best is not None and best.tgs > 0.0 else Plan(0, 0, 0, 0.0, 0)
 
 
 def best_window(p: float, D: Affine, V_of_w: Sequence[Affine], b: float) -> tuple:

@@ -337,17 +337,22 @@ def verify_step(spec: M.ModelSpec, weights: dict, caches, x0: np.ndarray, drafts
     for b in range(B):
         out[b, :a[b]] = drafts[b, best[b], :a[b]]
         out[b, a[b]] = ch_y[b, best[b]]
-        # rollback: bring the kept chain's entries to positions L+1..L+a
-        c = caches[b]
-        L = c.length
-        for i in range(1, a[b] + 1):
-            src = L + 1 + best[b] * k + (i - 1)
-            for l in range(spec.n_layers):
-                c.k[l][L + i] = c.k[l][src]
-                c.v[l][L + i] = c.v[l][src]
-        c.length = L + a[b] + 1
+        rollback(caches[b], int(best[b]), int(a[b]), k)
     return StepResult(a, out, best, logits, ch_a, ch_y, v.accept_margin.reshape(B, N),
                       v.draw_margin.reshape(B, N), v.zero_residual.reshape(B, N), margins)
+
+
+def rollback(cache: M.SeqCache, best: int, a: int, k: int) -> None:
+    """Step 5: after a pass that appended x0 and N chains of k drafts at slots L, L+1.., keep x0 and the `a`
+    accepted drafts of chain `best` at slots L..L+a (chain c's draft i sits at slot L + 1 + c*k + (i-1)); the
+    length becomes L + a + 1 and everything beyond it is dead."""
+    L = cache.length
+    for i in range(1, a + 1):
+        src = L + 1 + best * k + (i - 1)
+        for l in range(len(cache.k)):
+            cache.k[l][L + i] = cache.k[l][src]
+            cache.v[l][L + i] = cache.v[l][src]
+    cache.length = L + a + 1
 
 
 def prefill(spec: M.ModelSpec, weights: dict, cache: M.SeqCache, tokens: np.ndarray) -> np.ndarray:

@@ -12,6 +12,12 @@ import workloads as W
 
 LOGIT_TOL = {"bf16": 2e-2, "fp32": 1e-4}      # absolute, on logits
 MARGIN = 1e-3                                  # decisions closer than this are exempt from exact parity
+# Drift of two correct implementations over many layers (tests/test_oracle_drift.py shows it on the CPU, with
+# the oracle against a float32-accumulating copy of itself): the rms of the logit difference, in units of the
+# logits' spread, stays below DRIFT_RMS_PER_SQRT_LAYER * sqrt(n_layers) (measured 2.1e-3 to 2.7e-3 per sqrt-layer
+# at d_model 1024 and 2048), and the largest of millions of differences below DRIFT_MAX_OVER_RMS times that.
+DRIFT_RMS_PER_SQRT_LAYER = 4e-3
+DRIFT_MAX_OVER_RMS = 6.5
 
 
 def spec_of(shape: W.Shape) -> M.ModelSpec:
@@ -84,7 +90,11 @@ class Case:
             draft_lens=None if draft_lens is None else torch.as_tensor(draft_lens, dtype=torch.int32, device=dev),
             want_logits=True)
         torch.cuda.synchronize()
-        return r, {k_: v.cpu().numpy() for k_, v in out.items()}
+        g = DeviceOut({k_: v.cpu().numpy() for k_, v in out.items()})
+        g.inputs = dict(drafts=np.asarray(drafts), q=None if draft_probs is None else draft_probs.numpy(), u=uniforms,
+                        draft_lens=draft_lens, verify_mode=self.verify_mode, sample_mode=self.sample_mode,
+                        temperature=self.temperature)
+        return r, g
 
     def device_lengths(self):
         return np.array([self.ver.seq_len(b) for b in range(len(self.lengths))])
@@ -93,16 +103,81 @@ class Case:
         self.ver.close()
 
 
-def compare_step(r: OV.StepResult, g: dict, dtype: str, k: int):
-    """Logits within tolerance everywhere; accepted lengths, kept chains and emitted tokens identical,
-    except for requests where a decision the oracle took was closer than the margin.  The margin is
-    MARGIN (1e-3), widened to twice the logit error actually seen on that request's rows: two sets of
-    logits that differ by e cannot be expected to agree on a decision whose margin is below 2e (both
-    the compared logit and the log-sum-exp move).  Mismatches with a margin above 1e-3 are counted
-    separately.  Returns (max logit error, number of exempted requests, requests that diverged)."""
+class DeviceOut(dict):
+    """Results of a device step (a dict of arrays) that also remembers what the step was given."""
+    inputs: dict
+
+
+def decide(logits, drafts, q, u, verify_mode, sample_mode, temperature, draft_lens=None, first_request=0):
+    """The oracle's accept / reject + draw + chain choice on given logits [B, 1+N*k, V]: accepted length, emitted
+    tokens, kept chain and the smallest decision margin per request (over all chains: a decision of any chain
+    can change which one is kept).  first_request: index in the step's batch of the first of these requests (the
+    exponential-race draw is keyed by it)."""
+    B, N, k = drafts.shape
+    V = logits.shape[-1]
+    per_chain = np.empty((B, N, k + 1, V))
+    for c in range(N):
+        per_chain[:, c, 0] = logits[:, 0]
+        per_chain[:, c, 1:] = logits[:, 1 + c * k: 1 + (c + 1) * k]
+    S = B * N
+    lens = None if draft_lens is None else np.repeat(np.asarray(draft_lens), N)
+    if verify_mode == OV.GREEDY:
+        v = OV.verify_greedy(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k), lens)
+    elif verify_mode == OV.MATCH:
+        v = OV.verify_match(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
+                            np.repeat(np.asarray(u)[:, :1, :], N, axis=1).reshape(S, k + 1),
+                            np.repeat(first_request + np.arange(B), N), temperature, sample_mode, lens)
+    else:
+        v = OV.verify_stochastic(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
+                                 None if q is None else np.asarray(q).reshape(S, k, V), np.asarray(u).reshape(S, k + 1),
+                                 np.uint64(first_request * N) + np.arange(S, dtype=np.uint64), temperature, sample_mode, lens)
+    a = v.accepted.reshape(B, N)
+    best = np.argmax(a, axis=1)
+    out = np.full((B, k + 1), -1, dtype=np.int64)
+    for b in range(B):
+        ab = a[b, best[b]]
+        out[b, :ab] = drafts[b, best[b], :ab]
+        out[b, ab] = v.token.reshape(B, N)[b, best[b]]
+    margin = np.minimum(v.accept_margin, v.draw_margin).reshape(B, N).min(axis=1)
+    return a[np.arange(B), best], out, best, margin
+
+
+def check_decisions_on_own_logits(g: DeviceOut, rows=None):
+    """The stated decision tolerance, with nothing else in the way: the oracle's rule applied to the logits the
+    DEVICE produced (same drafts, draft distributions and uniforms) must give the device's accepted lengths,
+    kept chains and tokens bit for bit, except for requests where a margin of that evaluation is below 1e-3.
+    Returns the number of requests exempted that way."""
+    i = g.inputs
+    sel = np.arange(len(g["accepted_len"])) if rows is None else np.asarray(rows)
+    a, out, best, margin = decide(g["logits"].astype(np.float64), i["drafts"], i["q"], i["u"], i["verify_mode"],
+                                  i["sample_mode"], i["temperature"], i["draft_lens"])
+    exempt = 0
+    for b in sel:
+        same = g["accepted_len"][b] == a[b] and g["best_chain"][b] == best[b] and np.array_equal(g["out_tokens"][b], out[b])
+        if not same:
+            assert margin[b] < MARGIN, (f"request {b}: device a={g['accepted_len'][b]} tokens={g['out_tokens'][b]} chain="
+                                        f"{g['best_chain'][b]}; the rule on the device's own logits gives a={a[b]} "
+                                        f"tokens={out[b]} chain={best[b]} with margin {margin[b]}")
+            exempt += 1
+    return exempt
+
+
+def compare_step(r: OV.StepResult, g: dict, dtype: str, k: int, check_own: bool = True):
+    """A device step against the oracle's, under the stated tolerances and nothing wider:
+      1. logits within LOGIT_TOL (2e-2 bf16, 1e-4 fp32) everywhere;
+      2. the device's decisions are those of the oracle's rule on the device's own logits, except at margins
+         below 1e-3 (check_decisions_on_own_logits; strict, no budget);
+      3. end to end, accepted lengths, kept chains and tokens equal the oracle's, except for requests where a
+         decision of the oracle was closer than twice the logit tolerance (two sets of logits that may differ
+         by LOGIT_TOL cannot agree on a decision whose margin is below 2 LOGIT_TOL: the compared logit and the
+         log-sum-exp both move).  Of those, the ones with an oracle margin above 1e-3 are counted in
+         compare_step.beyond_margin and held to a fixed budget of max(1, B // 8) per step.
+    Returns (max logit error, number of exempted requests, requests that diverged)."""
     diff = np.abs(g["logits"].astype(np.float64) - r.logits)
     err = float(np.max(diff))
     assert err < LOGIT_TOL[dtype], f"logits differ by {err}"
+    if check_own and isinstance(g, DeviceOut):
+        check_decisions_on_own_logits(g)
     B = len(r.accepted_len)
     exempt, diverged = 0, []
     compare_step.beyond_margin = 0
@@ -113,15 +188,15 @@ def compare_step(r: OV.StepResult, g: dict, dtype: str, k: int):
         if same:
             continue
         margin = min(float(np.min(r.accept_margin[b])), float(np.min(r.draw_margin[b])))
-        allowed = max(MARGIN, 2.0 * float(np.max(diff[b])))
-        assert margin < allowed, (f"request {b}: device a={g['accepted_len'][b]} tokens={g['out_tokens'][b]} "
-                                  f"chain={g['best_chain'][b]} vs oracle a={r.accepted_len[b]} "
-                                  f"tokens={r.out_tokens[b]} chain={r.best_chain[b]}; smallest margin {margin}, "
-                                  f"logit error on its rows {float(np.max(diff[b]))}")
+        assert margin < 2.0 * LOGIT_TOL[dtype], (f"request {b}: device a={g['accepted_len'][b]} tokens={g['out_tokens'][b]} "
+                                                 f"chain={g['best_chain'][b]} vs oracle a={r.accepted_len[b]} "
+                                                 f"tokens={r.out_tokens[b]} chain={r.best_chain[b]}; smallest margin {margin}, "
+                                                 f"logit error on its rows {float(np.max(diff[b]))}")
         if margin >= MARGIN:
             compare_step.beyond_margin += 1
         exempt += 1
         diverged.append(b)
+    assert compare_step.beyond_margin <= max(1, B // 8), f"{compare_step.beyond_margin} requests diverged beyond the 1e-3 margin"
     return err, exempt, diverged
 
 
