@@ -61,6 +61,26 @@ int sv_op_sample(const float *logits, const int32_t *drafts, const float *draft_
  * type).  n = 1 + N*k.  Lengths are not changed. */
 int sv_op_attention(sv_ctx *, const int32_t *seq_ids, int B, int n, int k, int layer, const void *q, void *out);
 
+/* One decoder layer of the parallel verification pass on given residual rows (Section 3, "Opportunity": the
+ * pass of the trained model over the drafted tokens, here one layer of it at a time so that every layer can be
+ * held to the oracle on the oracle's own input).  For the listed sequences (HOST array seq_ids[B], live length
+ * L_b) and n = 1 + N*k new rows per request in verify_step's row order, h_in [B*n, d_model] fp32 is the residual
+ * stream entering layer `layer`; h_out [B*n, d_model] fp32 (may alias h_in) receives it after the layer's
+ * attention and feed-forward blocks, through exactly the launches verify_step makes for that layer: the rows'
+ * K/V entries of this layer are written to cache slots L_b .. L_b+n-1 as in a step, lengths are not changed.
+ * Mixture-of-experts models: top_ids / top_w (device [B*n, top_k], optional) receive the routing of the rows. */
+int sv_op_layer(sv_ctx *, const int32_t *seq_ids, int B, int n, int k, int layer, const float *h_in, float *h_out,
+                int32_t *top_ids, float *top_w);
+
+/* The rollback stage alone (the last step of a verification: the first rejected draft and everything after it
+ * are dropped, Section 3 "Opportunity"): for the listed sequences (HOST array seq_ids[B], live length L_b), whose
+ * cache slots L_b .. L_b + N*k hold x0 and N chains of k drafts as a pass leaves them, the accepted_len[b] (DEVICE,
+ * 0..k) first entries of chain best_chain[b] (DEVICE, 0..N-1) are moved next to x0, to slots L_b+1 .. L_b+a, in
+ * every layer; verdicts outside those ranges move nothing.  commit != 0: the live lengths advance by a_b + 1 as
+ * at the end of verify_step; commit == 0: lengths stay (the same verdicts can be applied again, for timing). */
+int sv_op_rollback(sv_ctx *, const int32_t *seq_ids, int B, int N, int k, const int32_t *accepted_len,
+                   const int32_t *best_chain, int commit);
+
 /* The mixture-of-experts feed-forward on its own (the MoE model the paper evaluates, Section 5.3): softmax
  * router over E experts, top_k largest probabilities (lowest id among equals), renormalised; per selected
  * expert (silu(x Wg^T) * (x Wu^T)) Wd^T with the product silu * up rounded to bf16; out[t] = weighted sum.
@@ -86,6 +106,20 @@ int sv_seq_set_lens(sv_ctx *, const int32_t *seq_ids, const int32_t *lens, int n
 enum { SV_PROF_GEMM = 0, SV_PROF_ATTENTION = 1, SV_PROF_SAMPLER = 2, SV_PROF_ROLLBACK = 3, SV_PROF_MOE = 4, SV_PROF_KINDS = 5 };
 int sv_profile_enable(sv_ctx *, unsigned kind_mask);
 int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launches /* host */);
+
+/* Rooflines of this very GPU, measured (all pointers DEVICE unless stated; both calls synchronise `stream`).
+ * sv_probe_mfma_bf16: 256 work-groups of four waves run `iters` rounds of eight independent
+ *   v_mfma_f32_32x32x16_bf16 on operands held in registers (read once from `operands`, at least 256*256*128
+ *   bytes: random bf16 values give the rate on real data, zeros the unthrottled one); `sink` takes 65536 floats;
+ *   *tflops (HOST) = achieved dense bf16 rate.
+ * sv_probe_hbm_copy: `reps` plain copies of `bytes` (a multiple of 16, at least 1 MiB, both buffers 16-byte
+ *   aligned, choose it far larger than the caches); *gbs_each_way (HOST) = bytes copied per second in GB/s, i.e.
+ *   that much read and as much written.
+ * sv_probe_hbm_read: `reps` plain read-only passes over `bytes` (same constraints); `sink` takes 4 bytes;
+ *   *gbs (HOST) = bytes read per second in GB/s. */
+int sv_probe_mfma_bf16(const void *operands, size_t operand_bytes, float *sink, int iters, void *stream, double *tflops);
+int sv_probe_hbm_copy(const void *src, void *dst, size_t bytes, int reps, void *stream, double *gbs_each_way);
+int sv_probe_hbm_read(const void *src, size_t bytes, int reps, void *sink, void *stream, double *gbs);
 
 /* Tuning / diagnostic knobs of a context.
  *   SV_OPT_GEMM_VARIANT  kernel / work-group tile of the bf16 projections (0..6; -1 = per shape, default)

@@ -25,8 +25,8 @@ EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_prefill_batch", "verify_step",
-    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
-    "sv_profile_read",
+    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_op_layer", "sv_op_rollback", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
+    "sv_profile_read", "sv_probe_mfma_bf16", "sv_probe_hbm_copy", "sv_probe_hbm_read",
     "sv_plan_accept_prob", "sv_plan_tau", "sv_plan_decoupled", "sv_plan_best_window", "sv_fit_affine",
 ]
 
@@ -112,9 +112,15 @@ def load_library() -> C.CDLL:
     lib.sv_op_moe_ffn.argtypes = [C.c_void_p] * 4 + [C.c_int] * 5 + [C.c_void_p, C.c_size_t] + [C.c_void_p] * 4
     lib.sv_op_attention.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p]
+    lib.sv_op_layer.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_void_p]
+    lib.sv_op_rollback.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int]
     lib.sv_seq_set_lens.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
     lib.sv_profile_enable.argtypes = [C.c_void_p, C.c_uint]
     lib.sv_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+    lib.sv_probe_mfma_bf16.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_double)]
+    lib.sv_probe_hbm_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.POINTER(C.c_double)]
+    lib.sv_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     lib.sv_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
     lib.sv_plan_accept_prob.restype = C.c_double
     lib.sv_plan_accept_prob.argtypes = [C.c_double, C.c_int, C.c_int]
@@ -309,6 +315,27 @@ class Verifier:
         self._check(self.lib.sv_op_attention(self.ctx, ids, B, n, k, layer, _ptr(q), _ptr(out)))
         return out
 
+    def op_layer(self, seq_ids, n: int, k: int, layer: int, h: torch.Tensor, want_routing: bool = False):
+        """h fp32 [B*n, d_model] entering `layer` -> the residual stream after it (and, for mixture-of-experts
+        models with want_routing, the rows' expert ids [B*n, top_k] and weights)."""
+        B = len(seq_ids)
+        assert h.dtype == torch.float32 and h.is_contiguous() and tuple(h.shape) == (B * n, self.model["d_model"])
+        out = torch.empty_like(h)
+        ids = (C.c_int32 * B)(*[int(s) for s in seq_ids])
+        top_ids = top_w = None
+        if want_routing and self.model.get("n_experts", 0):
+            top_ids = torch.empty((B * n, self.model["top_k"]), dtype=torch.int32, device=self.device)
+            top_w = torch.empty((B * n, self.model["top_k"]), dtype=torch.float32, device=self.device)
+        self._check(self.lib.sv_op_layer(self.ctx, ids, B, n, k, layer, _ptr(h), _ptr(out), _ptr(top_ids), _ptr(top_w)))
+        return (out, top_ids, top_w) if want_routing else out
+
+    def op_rollback(self, seq_ids, N: int, k: int, accepted_len: torch.Tensor, best_chain: torch.Tensor, commit: bool = True):
+        """The rollback stage alone on given verdicts (int32 device tensors [B])."""
+        B = len(seq_ids)
+        assert accepted_len.dtype == torch.int32 and best_chain.dtype == torch.int32 and accepted_len.numel() == B == best_chain.numel()
+        ids = (C.c_int32 * B)(*[int(s) for s in seq_ids])
+        self._check(self.lib.sv_op_rollback(self.ctx, ids, B, N, k, _ptr(accepted_len), _ptr(best_chain), 1 if commit else 0))
+
     def seq_set_lens(self, seq_ids, lens):
         n = len(seq_ids)
         ids = (C.c_int32 * n)(*[int(s) for s in seq_ids])
@@ -427,6 +454,42 @@ def op_sample(logits: torch.Tensor, drafts: torch.Tensor, draft_probs, uniforms,
     if rc != 0:
         raise SvError(rc, "sv_op_sample")
     return acc, toks, best
+
+
+def probe_peaks(device="cuda:0", mfma_iters: int = 20000, copy_bytes: int = 1 << 30, copy_reps: int = 5) -> dict:
+    """The two micro-benchmarked rooflines of this GPU: dense bf16 MFMA rate on random operands (and on zeros),
+    and the rate of a plain device copy."""
+    dev = torch.device(device)
+    out = {}
+    sink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+    for name, ops in (("mfma_bf16_tflops_random_operands", torch.randn(256 * 256 * 64, device=dev).to(torch.bfloat16)),
+                      ("mfma_bf16_tflops_zero_operands", torch.zeros(256 * 256 * 64, dtype=torch.bfloat16, device=dev))):
+        v = C.c_double()
+        rc = lib().sv_probe_mfma_bf16(_ptr(ops), ops.numel() * 2, _ptr(sink), mfma_iters, _stream_ptr(), C.byref(v))
+        if rc != 0:
+            raise SvError(rc, "sv_probe_mfma_bf16")
+        out[name] = v.value
+    out["hbm_copy_gbs_read_plus_write"] = 2.0 * probe_copy(copy_bytes, copy_reps, dev)
+    src = torch.ones(copy_bytes // 4, dtype=torch.float32, device=dev)
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    v = C.c_double()
+    rc = lib().sv_probe_hbm_read(_ptr(src), copy_bytes, copy_reps, _ptr(flag), _stream_ptr(), C.byref(v))
+    if rc != 0:
+        raise SvError(rc, "sv_probe_hbm_read")
+    out["hbm_read_gbs"] = v.value
+    return out
+
+
+def probe_copy(nbytes: int = 1 << 30, reps: int = 1, device="cuda:0") -> float:
+    """`reps` plain device copies of nbytes (after one untimed warm-up copy); GB/s copied (as much read as written)."""
+    dev = torch.device(device)
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    v = C.c_double()
+    rc = lib().sv_probe_hbm_copy(_ptr(src), _ptr(dst), nbytes, reps, _stream_ptr(), C.byref(v))
+    if rc != 0:
+        raise SvError(rc, "sv_probe_hbm_copy")
+    return v.value
 
 
 # ---- planner (host-only entry points of specverify_plan.h) ----

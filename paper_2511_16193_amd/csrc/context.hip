@@ -591,8 +591,40 @@ static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int 
     return SV_OK;
 }
 
-// Rows are already described by batch_seq / last_tokens / drafts.  Leaves logits in the workspace.
-static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_tokens, const int32_t* drafts, int max_len_ub) {
+// Row preparation of a pass: positions, cache slots, rotary table, token ids of the B * n new rows.
+static int prepare_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_tokens, const int32_t* drafts) {
+    const sv_model& m = c->model;
+    const Layout& L = c->lay;
+    RowPrep rp;
+    rp.batch_seq = c->at<int32_t>(L.batch_seq); rp.seq_len = c->at<int32_t>(L.seq_len);
+    rp.last_tokens = last_tokens; rp.drafts = drafts;
+    rp.row_tok = c->at<int32_t>(L.row_tok); rp.row_pos = c->at<int32_t>(L.row_pos); rp.row_slot = c->at<int32_t>(L.row_slot);
+    rp.rope = c->at<float>(L.rope);
+    rp.B = B; rp.n = n; rp.k = k; rp.head_dim = m.head_dim; rp.vocab = m.vocab; rp.rope_theta = m.rope_theta;
+    rp.tok_matrix = c->tok_matrix; rp.tok_len = c->tok_len; rp.tok_ld = c->tok_ld; rp.tok_col0 = c->tok_col0;
+    SV_HIP(c, prep_rows(rp, c->stream));
+    return SV_OK;
+}
+
+// Residual add of what the previous projection left behind, then RMSNorm into the packed operand buffer.
+// pending > 0: that many split-K planes in `part`; 0: nothing to add; -1: the expert outputs of a
+// mixture-of-experts layer, still to be combined with the routing weights and added.
+static int add_norm(sv_ctx* c, int T, int pending, const void* gain) {
+    const sv_model& m = c->model;
+    const Layout& L = c->lay;
+    float* h = c->at<float>(L.h);
+    void* a_norm = c->at<void>(L.a_norm);
+    if (pending < 0)
+        SV_HIP(c, add_rmsnorm_experts(h, c->at<float>(L.moe_y), c->at<int32_t>(L.moe_inv), c->at<float>(L.moe_w), m.top_k, gain, a_norm,
+                                      T, m.d_model, m.rms_eps, c->packed, c->stream));
+    else
+        SV_HIP(c, add_rmsnorm(h, c->at<float>(L.part), pending, gain, a_norm, m.dtype, T, m.d_model, m.rms_eps, c->packed, c->stream));
+    return SV_OK;
+}
+
+// One decoder layer over the prepared rows.  On entry the residual stream h lacks `pending` (see add_norm) of
+// the previous layer; on exit it lacks this layer's feed-forward output, described by the new `pending`.
+static int layer_rows(sv_ctx* c, int l, int B, int n, int k, int max_len_ub, int& pending) {
     const sv_model& m = c->model;
     const Layout& L = c->lay;
     const int T = B * n, d = m.d_model, qw = m.n_q_heads * m.head_dim, qkvw = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
@@ -601,87 +633,81 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
     float* part = c->at<float>(L.part);
     void* a_norm = c->at<void>(L.a_norm);
 
-    RowPrep rp;
-    rp.batch_seq = c->at<int32_t>(L.batch_seq); rp.seq_len = c->at<int32_t>(L.seq_len);
-    rp.last_tokens = last_tokens; rp.drafts = drafts;
-    rp.row_tok = c->at<int32_t>(L.row_tok); rp.row_pos = c->at<int32_t>(L.row_pos); rp.row_slot = c->at<int32_t>(L.row_slot);
-    rp.rope = c->at<float>(L.rope);
-    rp.B = B; rp.n = n; rp.k = k; rp.head_dim = m.head_dim; rp.vocab = m.vocab; rp.rope_theta = m.rope_theta;
-    rp.tok_matrix = c->tok_matrix; rp.tok_len = c->tok_len; rp.tok_ld = c->tok_ld; rp.tok_col0 = c->tok_col0;
-    SV_HIP(c, prep_rows(rp, st));
-    SV_HIP(c, embed_rows(c->embed, m.dtype, rp.row_tok, h, T, d, st));
+    SV_TRY(add_norm(c, T, pending, c->ln1[l]));
+    pending = 0;
+    int s_qkv = 1;
+    SV_TRY(gemm(c, a_norm, c->wqkv[l], part, T, qkvw, d, &s_qkv));
+    RopeAppend ra;
+    ra.qkv_part = part; ra.S = s_qkv; ra.rope = c->at<float>(L.rope); ra.row_slot = c->at<int32_t>(L.row_slot);
+    ra.batch_seq = c->at<int32_t>(L.batch_seq);
+    ra.page_table = c->at<int32_t>(L.page_table); ra.max_pages_per_seq = c->rt.max_pages_per_seq;
+    ra.q_out = c->at<void>(L.q); ra.pool = c->rt.kv_pool; ra.geom = c->geom; ra.layer = l;
+    ra.T = T; ra.n = n; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.dtype = m.dtype;
+    SV_HIP(c, rope_append(ra, st));
 
-    int pending = 0;      // split-K partials of the previous projection, still to be added to h;
-                          // -1: the expert outputs of the previous layer, still to be combined and added
-    auto norm = [&](const void* gain) -> hipError_t {
-        if (pending < 0)
-            return add_rmsnorm_experts(h, c->at<float>(L.moe_y), c->at<int32_t>(L.moe_inv), c->at<float>(L.moe_w), m.top_k, gain, a_norm,
-                                       T, d, m.rms_eps, c->packed, st);
-        return add_rmsnorm(h, part, pending, gain, a_norm, m.dtype, T, d, m.rms_eps, c->packed, st);
-    };
-    for (int l = 0; l < m.n_layers; ++l) {
-        SV_HIP(c, norm(c->ln1[l]));
-        int s_qkv = 1;
-        SV_TRY(gemm(c, a_norm, c->wqkv[l], part, T, qkvw, d, &s_qkv));
-        RopeAppend ra;
-        ra.qkv_part = part; ra.S = s_qkv; ra.rope = rp.rope; ra.row_slot = rp.row_slot; ra.batch_seq = rp.batch_seq;
-        ra.page_table = c->at<int32_t>(L.page_table); ra.max_pages_per_seq = c->rt.max_pages_per_seq;
-        ra.q_out = c->at<void>(L.q); ra.pool = c->rt.kv_pool; ra.geom = c->geom; ra.layer = l;
-        ra.T = T; ra.n = n; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.dtype = m.dtype;
-        SV_HIP(c, rope_append(ra, st));
-
-        AttnArgs aa;
-        aa.q = ra.q_out; aa.pool = c->rt.kv_pool; aa.geom = c->geom; aa.layer = l;
-        aa.page_table = ra.page_table; aa.max_pages_per_seq = c->rt.max_pages_per_seq;
-        aa.batch_seq = rp.batch_seq; aa.seq_len = rp.seq_len; aa.out = c->at<void>(L.attn);
-        aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml); aa.rows_pad = L.rows_pad; aa.row_groups = 1;
-        aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
-        aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work; aa.req_chunk = c->at<int32_t>(L.req_chunk);
-        aa.out_packed = c->packed;
-        aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
-        aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
-        aa.n_work_dev = nullptr; aa.grid_items = 0;
-        if (c->graph_launch_shape) {      // nothing in the launch may depend on the lengths
-            aa.max_chunks = L.max_chunks;
-            aa.n_work_dev = c->at<int32_t>(L.req_chunk) + 2 * c->rt.max_batch;
-            aa.grid_items = B * L.max_chunks;
-        }
-        {
-            ProfScope prof(c, SV_PROF_ATTENTION);
-            SV_HIP(c, attention(aa, st));
-        }
-
-        int s_o = 1;
-        SV_TRY(gemm(c, aa.out, c->wo[l], part, T, d, qw, &s_o));
-        SV_HIP(c, add_rmsnorm(h, part, s_o, c->ln2[l], a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
-        if (m.n_experts > 0) {
-            MoeArgs ma;
-            ma.a = (const bf16_t*)a_norm; ma.w_router = (const bf16_t*)c->wrouter[l];
-            ma.w_gate_up = (const bf16_t*)c->wgu[l]; ma.w_down = (const bf16_t*)c->wdown[l];
-            ma.top_ids = c->at<int32_t>(L.moe_ids); ma.top_w = c->at<float>(L.moe_w); ma.router_logits = c->at<float>(L.moe_logits);
-            ma.cnt = c->at<int32_t>(L.moe_cnt); ma.tile_off = c->at<int32_t>(L.moe_off);
-            ma.perm = c->at<int32_t>(L.moe_perm); ma.inv = c->at<int32_t>(L.moe_inv);
-            ma.act = c->at<bf16_t>(L.moe_act); ma.y = c->at<float>(L.moe_y); ma.out = nullptr;   // combined by the next norm
-            ma.T = T; ma.d = d; ma.E = m.n_experts; ma.top_k = m.top_k; ma.F = m.d_expert;
-            ProfScope prof(c, SV_PROF_MOE);
-            SV_HIP(c, moe_ffn(ma, st));
-            pending = -1;
-            continue;
-        }
-        if (c->packed && m.d_ff % 64 == 0) {
-            // gate/up projection with SwiGLU in its epilogue: the [T, 2F] fp32 intermediate never exists
-            ProfScope prof(c, SV_PROF_GEMM);
-            SV_HIP(c, gemm_bf16_ws_glu((const bf16_t*)a_norm, (const bf16_t*)c->wgu[l], c->at<bf16_t>(L.act), T, m.d_ff, d, st));
-        } else {
-            int s_gu = 1;
-            SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
-            SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, c->packed, st));
-        }
-        SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
+    AttnArgs aa;
+    aa.q = ra.q_out; aa.pool = c->rt.kv_pool; aa.geom = c->geom; aa.layer = l;
+    aa.page_table = ra.page_table; aa.max_pages_per_seq = c->rt.max_pages_per_seq;
+    aa.batch_seq = ra.batch_seq; aa.seq_len = c->at<int32_t>(L.seq_len); aa.out = c->at<void>(L.attn);
+    aa.part_o = c->at<float>(L.part_o); aa.part_ml = c->at<float>(L.part_ml); aa.rows_pad = L.rows_pad; aa.row_groups = 1;
+    aa.B = B; aa.n = n; aa.k = k; aa.Hq = m.n_q_heads; aa.Hkv = m.n_kv_heads; aa.hd = m.head_dim; aa.dtype = m.dtype;
+    aa.chunk_keys = c->attn_chunk; aa.work = c->at<int32_t>(L.work); aa.n_work = c->n_work; aa.req_chunk = c->at<int32_t>(L.req_chunk);
+    aa.out_packed = c->packed;
+    aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
+    aa.max_chunks = std::min(L.max_chunks, (max_len_ub + n + c->attn_chunk - 1) / c->attn_chunk);
+    aa.n_work_dev = nullptr; aa.grid_items = 0;
+    if (c->graph_launch_shape) {      // nothing in the launch may depend on the lengths
+        aa.max_chunks = L.max_chunks;
+        aa.n_work_dev = c->at<int32_t>(L.req_chunk) + 2 * c->rt.max_batch;
+        aa.grid_items = B * L.max_chunks;
     }
-    SV_HIP(c, norm(c->final_norm));
+    {
+        ProfScope prof(c, SV_PROF_ATTENTION);
+        SV_HIP(c, attention(aa, st));
+    }
+
+    int s_o = 1;
+    SV_TRY(gemm(c, aa.out, c->wo[l], part, T, d, qw, &s_o));
+    SV_HIP(c, add_rmsnorm(h, part, s_o, c->ln2[l], a_norm, m.dtype, T, d, m.rms_eps, c->packed, st));
+    if (m.n_experts > 0) {
+        MoeArgs ma;
+        ma.a = (const bf16_t*)a_norm; ma.w_router = (const bf16_t*)c->wrouter[l];
+        ma.w_gate_up = (const bf16_t*)c->wgu[l]; ma.w_down = (const bf16_t*)c->wdown[l];
+        ma.top_ids = c->at<int32_t>(L.moe_ids); ma.top_w = c->at<float>(L.moe_w); ma.router_logits = c->at<float>(L.moe_logits);
+        ma.cnt = c->at<int32_t>(L.moe_cnt); ma.tile_off = c->at<int32_t>(L.moe_off);
+        ma.perm = c->at<int32_t>(L.moe_perm); ma.inv = c->at<int32_t>(L.moe_inv);
+        ma.act = c->at<bf16_t>(L.moe_act); ma.y = c->at<float>(L.moe_y); ma.out = nullptr;   // combined by the next norm
+        ma.T = T; ma.d = d; ma.E = m.n_experts; ma.top_k = m.top_k; ma.F = m.d_expert;
+        ProfScope prof(c, SV_PROF_MOE);
+        SV_HIP(c, moe_ffn(ma, st));
+        pending = -1;
+        return SV_OK;
+    }
+    if (c->packed && m.d_ff % 64 == 0) {
+        // gate/up projection with SwiGLU in its epilogue: the [T, 2F] fp32 intermediate never exists
+        ProfScope prof(c, SV_PROF_GEMM);
+        SV_HIP(c, gemm_bf16_ws_glu((const bf16_t*)a_norm, (const bf16_t*)c->wgu[l], c->at<bf16_t>(L.act), T, m.d_ff, d, st));
+    } else {
+        int s_gu = 1;
+        SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
+        SV_HIP(c, swiglu(part, s_gu, c->at<void>(L.act), m.dtype, T, m.d_ff, c->packed, st));
+    }
+    SV_TRY(gemm(c, c->at<void>(L.act), c->wdown[l], part, T, d, m.d_ff, &pending));
+    return SV_OK;
+}
+
+// Rows are already described by batch_seq / last_tokens / drafts.  Leaves logits in the workspace.
+static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_tokens, const int32_t* drafts, int max_len_ub) {
+    const sv_model& m = c->model;
+    const Layout& L = c->lay;
+    const int T = B * n;
+    SV_TRY(prepare_rows(c, B, n, k, last_tokens, drafts));
+    SV_HIP(c, embed_rows(c->embed, m.dtype, c->at<int32_t>(L.row_tok), c->at<float>(L.h), T, m.d_model, c->stream));
+    int pending = 0;
+    for (int l = 0; l < m.n_layers; ++l) SV_TRY(layer_rows(c, l, B, n, k, max_len_ub, pending));
+    SV_TRY(add_norm(c, T, pending, c->final_norm));
     int one = 1;
-    SV_TRY(gemm(c, a_norm, c->lm_head, c->at<float>(L.logits), T, m.vocab, d, &one, false));
+    SV_TRY(gemm(c, c->at<void>(L.a_norm), c->lm_head, c->at<float>(L.logits), T, m.vocab, m.d_model, &one, false));
     return SV_OK;
 }
 
@@ -1008,6 +1034,53 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
     aa.n_work_dev = nullptr; aa.grid_items = 0;
     SV_HIP(c, attention(aa, c->stream));
+    return SV_OK;
+}
+
+extern "C" int sv_op_layer(sv_ctx* c, const int32_t* seq_ids, int B, int n, int k, int layer, const float* h_in,
+                           float* h_out, int32_t* top_ids, float* top_w) {
+    if (!c || !seq_ids || !h_in || !h_out) return SV_EINVAL;
+    if (B <= 0 || B > c->rt.max_batch || n <= 0 || B * n > c->lay.T || k < 0 || layer < 0 || layer >= c->model.n_layers ||
+        (k > 0 && (n - 1) % k != 0) || (k == 0 && n != 1))
+        return c->fail(SV_EINVAL, "layer %d over %d x %d rows (k=%d) outside the limits given at init", layer, B, n, k);
+    SV_TRY(stage_batch(c, seq_ids, B, n));
+    int max_ub = 0;
+    for (int b = 0; b < B; ++b) max_ub = std::max(max_ub, c->seqs[seq_ids[b]].len_ub);
+    const sv_model& m = c->model;
+    const Layout& L = c->lay;
+    const int T = B * n;
+    const size_t bytes = sizeof(float) * (size_t)T * m.d_model;
+    SV_TRY(prepare_rows(c, B, n, k, nullptr, nullptr));
+    SV_HIP(c, hipMemcpyAsync(c->at<float>(L.h), h_in, bytes, hipMemcpyDeviceToDevice, c->stream));
+    int pending = 0;
+    SV_TRY(layer_rows(c, layer, B, n, k, max_ub, pending));
+    // the feed-forward output is still pending: the residual add that the next layer's (or the final) norm would do
+    SV_TRY(add_norm(c, T, pending, c->final_norm));
+    SV_HIP(c, hipMemcpyAsync(h_out, c->at<float>(L.h), bytes, hipMemcpyDeviceToDevice, c->stream));
+    if (m.n_experts > 0) {
+        if (top_ids) SV_HIP(c, hipMemcpyAsync(top_ids, c->at<int32_t>(L.moe_ids), sizeof(int32_t) * (size_t)T * m.top_k, hipMemcpyDeviceToDevice, c->stream));
+        if (top_w) SV_HIP(c, hipMemcpyAsync(top_w, c->at<float>(L.moe_w), sizeof(float) * (size_t)T * m.top_k, hipMemcpyDeviceToDevice, c->stream));
+    }
+    return SV_OK;
+}
+
+extern "C" int sv_op_rollback(sv_ctx* c, const int32_t* seq_ids, int B, int N, int k, const int32_t* accepted_len,
+                              const int32_t* best_chain, int commit) {
+    if (!c || !seq_ids || !accepted_len || !best_chain) return SV_EINVAL;
+    if (B <= 0 || B > c->rt.max_batch || k < 0 || k > c->rt.max_k || N <= 0 || N > c->rt.max_chains)
+        return c->fail(SV_EINVAL, "batch %d / k %d / chains %d outside the limits given at init", B, k, N);
+    SV_TRY(stage_batch(c, seq_ids, B, 1 + N * k));       // the slots of a pass: L .. L + N*k
+    RollbackArgs rb;
+    rb.pool = c->rt.kv_pool; rb.geom = c->geom; rb.n_layers = c->model.n_layers; rb.dtype = c->model.dtype;
+    rb.page_table = c->at<int32_t>(c->lay.page_table); rb.max_pages_per_seq = c->rt.max_pages_per_seq;
+    rb.batch_seq = c->at<int32_t>(c->lay.batch_seq); rb.seq_len = c->at<int32_t>(c->lay.seq_len);
+    rb.accepted_len = accepted_len; rb.best_chain = best_chain; rb.B = B; rb.N = N; rb.k = k;
+    {
+        ProfScope prof(c, SV_PROF_ROLLBACK);
+        SV_HIP(c, rollback(rb, c->stream, commit != 0));
+    }
+    if (commit)
+        for (int b = 0; b < B; ++b) c->seqs[seq_ids[b]].len_ub += k + 1;
     return SV_OK;
 }
 

@@ -19,7 +19,8 @@ __global__ void prep_rows_kernel(RowPrep p) {
             const int col = min(p.tok_col0 + j, p.tok_len[b] - 1);
             tok = p.tok_matrix[(int64_t)b * p.tok_ld + col];
         } else {
-            tok = j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
+            // (a pass over given residual rows brings no tokens at all)
+            tok = !p.last_tokens ? 0 : j == 0 ? p.last_tokens[b] : p.drafts[(int64_t)b * (p.n - 1) + (j - 1)];
         }
         // ids arrive in device memory from another process and cannot be checked on the host: an id outside the
         // vocabulary is embedded as the nearest valid one (the sampler rejects such a draft whatever its row yields)

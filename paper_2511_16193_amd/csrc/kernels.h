@@ -140,6 +140,7 @@ struct RollbackArgs {
     const int32_t* best_chain;
     int B, N, k;
 };
-hipError_t rollback(const RollbackArgs& a, hipStream_t st);
+// move the kept chain's accepted K/V entries next to x0 (N > 1 only); commit: also advance the live lengths by a + 1
+hipError_t rollback(const RollbackArgs& a, hipStream_t st, bool commit = true);
 
 }  // namespace sv

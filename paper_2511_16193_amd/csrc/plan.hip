@@ -2,6 +2,7 @@
 // Algorithm 1).  Host-only: a few hundred double-precision operations per call.
 #include <cmath>
 #include <limits>
+#include <vector>
 #include "../../include/specverify_plan.h"
 
 namespace {
@@ -46,27 +47,48 @@ extern "C" double sv_plan_tau(double p, int w) {
     return tau_of(p, w);
 }
 
+// The plan search (what Algorithm 1 of Section 4.1 computes): every (verifier configuration, drafter size) pair
+// fixes a per-worker batch; every such pair is expanded into the draft windows worth trying; each resulting
+// candidate is scored by the speed model; the best-scoring candidate wins, the earliest among equals.
+namespace {
+
+struct Deployment {        // a verifier configuration paired with a drafter size
+    int config, g_d, g_v, batch, windows;
+};
+
+// All deployments in visiting order (configurations as given, drafter sizes ascending), each with the per-worker
+// batch it implies and the number of windows to try for it.
+std::vector<Deployment> enumerate_deployments(const sv_plan_input& in) {
+    std::vector<Deployment> all;
+    for (int c = 0; c < in.n_configs; ++c) {
+        const sv_affine& widest = in.V[(long long)c * in.W + in.W - 1];
+        for (int g_d = 1; g_d <= in.g_v[c]; ++g_d) {
+            const long long workers_times_batch = (long long)(g_d + in.g_v[c]) * in.B;
+            all.push_back({c, g_d, in.g_v[c], (int)((workers_times_batch + in.G - 1) / in.G),
+                           window_bound(in.D[g_d - 1], widest, in.W)});
+        }
+    }
+    return all;
+}
+
+}  // namespace
+
 extern "C" int sv_plan_decoupled(const sv_plan_input* in, sv_plan* out) {
     if (!in || !out || !in->g_v || !in->D || !in->V) return SV_EINVAL;
     if (in->B < 1 || in->G < 1 || in->W < 1 || in->n_configs < 1 || !prob_ok(in->p)) return SV_EINVAL;
     for (int c = 0; c < in->n_configs; ++c)
         if (in->g_v[c] < 1) return SV_EINVAL;
-    sv_plan best = {0, 0, 0, 0, 0.0};
-    for (int c = 0; c < in->n_configs; ++c) {
-        const int g_v = in->g_v[c];
-        const sv_affine* V = in->V + (long long)c * in->W;
-        for (int g_d = 1; g_d <= g_v; ++g_d) {
-            const long long num = (long long)(g_d + g_v) * in->B;
-            const int b = (int)((num + in->G - 1) / in->G);
-            const sv_affine& D = in->D[g_d - 1];
-            const int wm = window_bound(D, V[in->W - 1], in->W);
-            for (int w = 1; w <= wm; ++w) {
-                const double cur = tgs_of(in->p, w, D, V[w - 1], (double)b);
-                if (cur > best.tgs) best = {g_d, g_v, w, b, cur};
-            }
-        }
-    }
-    *out = best;
+    struct Scored { const Deployment* d; int w; double speed; };
+    const std::vector<Deployment> deployments = enumerate_deployments(*in);
+    std::vector<Scored> scored;
+    for (const Deployment& d : deployments)
+        for (int w = 1; w <= d.windows; ++w)
+            scored.push_back({&d, w, tgs_of(in->p, w, in->D[d.g_d - 1], in->V[(long long)d.config * in->W + w - 1], (double)d.batch)});
+    const Scored* winner = nullptr;                       // first of the largest positive speeds
+    for (const Scored& s : scored)
+        if (s.speed > (winner ? winner->speed : 0.0)) winner = &s;
+    if (winner) *out = {winner->d->g_d, winner->d->g_v, winner->w, winner->d->batch, winner->speed};
+    else *out = {0, 0, 0, 0, 0.0};
     return SV_OK;
 }
 

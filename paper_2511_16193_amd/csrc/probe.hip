@@ -1,0 +1,124 @@
+// Two micro-benchmarks that give the rooflines of this very GPU, as opposed to the data sheet's: a register-only
+// bf16 MFMA loop and a plain device copy.  The benchmark reports every kernel's rate against both.
+// Declared in include/specverify_ops.h.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/specverify.h"
+#include "../../include/specverify_ops.h"
+#include "common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+
+// One wave per SIMD, eight independent 32x32 accumulators, operands held in registers for the whole loop: nothing
+// but the matrix unit is busy.  The operands come from memory once (random values make the multipliers toggle, and
+// the chip's clock then settles well below what all-zero operands allow).
+__global__ __launch_bounds__(256, 1) void probe_mfma_kernel(const sv::u32x4* __restrict__ operands, float* __restrict__ sink, int iters) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    sv::bf16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = __builtin_bit_cast(sv::bf16x8, operands[(int64_t)t * 8 + i]);
+        b[i] = __builtin_bit_cast(sv::bf16x8, operands[(int64_t)t * 8 + 4 + i]);
+    }
+    floatx16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 1], acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    sink[t] = s;
+}
+
+// Plain copy, 16 bytes per lane, grid-stride: what a stream of reads and writes reaches on this part.
+__global__ __launch_bounds__(256) void probe_copy_kernel(const sv::u32x4* __restrict__ src, sv::u32x4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Plain read, 16 bytes per lane, four loads in flight per lane, grid-stride: what a read-only stream reaches (the
+// verify attention is one).  The xor of what was read goes to `sink` only if it matches a value it never has, so
+// that the loads are not optimised away and nothing is written.
+__global__ __launch_bounds__(256) void probe_read_kernel(const sv::u32x4* __restrict__ src, unsigned* __restrict__ sink, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    sv::u32x4 acc = {0, 0, 0, 0};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const sv::u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= src[i];
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = 1;
+}
+
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    bool ok() { return hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess; }
+    ~EventPair() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
+};
+
+}  // namespace
+
+extern "C" int sv_probe_mfma_bf16(const void* operands, size_t operand_bytes, float* sink, int iters, void* stream,
+                                  double* tflops) {
+    constexpr int kBlocks = 256;                          // one work-group per CU, one wave per SIMD
+    if (!operands || !sink || !tflops || iters <= 0 || operand_bytes < (size_t)kBlocks * 256 * 8 * 16) return SV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    EventPair ev;
+    if (!ev.ok()) return SV_EHIP;
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kBlocks), dim3(256), 0, st, (const sv::u32x4*)operands, sink, iters / 8 + 1);   // warm-up
+    if (hipEventRecord(ev.a, st) != hipSuccess) return SV_EHIP;
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kBlocks), dim3(256), 0, st, (const sv::u32x4*)operands, sink, iters);
+    if (hipEventRecord(ev.b, st) != hipSuccess || hipEventSynchronize(ev.b) != hipSuccess || hipGetLastError() != hipSuccess) return SV_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess || !(ms > 0.f)) return SV_EHIP;
+    *tflops = (double)kBlocks * 4 * iters * 8 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
+    return SV_OK;
+}
+
+extern "C" int sv_probe_hbm_copy(const void* src, void* dst, size_t bytes, int reps, void* stream, double* gbs_each_way) {
+    if (!src || !dst || !gbs_each_way || bytes < (1u << 20) || bytes % 16 != 0 || reps <= 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+        return SV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    EventPair ev;
+    if (!ev.ok()) return SV_EHIP;
+    const size_t n16 = bytes / 16;
+    const dim3 grid(256 * 16);
+    hipLaunchKernelGGL(probe_copy_kernel, grid, dim3(256), 0, st, (const sv::u32x4*)src, (sv::u32x4*)dst, n16);              // warm-up
+    if (hipEventRecord(ev.a, st) != hipSuccess) return SV_EHIP;
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(probe_copy_kernel, grid, dim3(256), 0, st, (const sv::u32x4*)src, (sv::u32x4*)dst, n16);
+    if (hipEventRecord(ev.b, st) != hipSuccess || hipEventSynchronize(ev.b) != hipSuccess || hipGetLastError() != hipSuccess) return SV_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess || !(ms > 0.f)) return SV_EHIP;
+    *gbs_each_way = (double)bytes * reps / (ms * 1e-3) / 1e9;
+    return SV_OK;
+}
+
+extern "C" int sv_probe_hbm_read(const void* src, size_t bytes, int reps, void* sink, void* stream, double* gbs) {
+    if (!src || !sink || !gbs || bytes < (1u << 20) || bytes % 16 != 0 || reps <= 0 || ((uintptr_t)src & 15)) return SV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    EventPair ev;
+    if (!ev.ok()) return SV_EHIP;
+    const size_t n16 = bytes / 16;
+    const dim3 grid(256 * 16);
+    hipLaunchKernelGGL(probe_read_kernel, grid, dim3(256), 0, st, (const sv::u32x4*)src, (unsigned*)sink, n16);                // warm-up
+    if (hipEventRecord(ev.a, st) != hipSuccess) return SV_EHIP;
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(probe_read_kernel, grid, dim3(256), 0, st, (const sv::u32x4*)src, (unsigned*)sink, n16);
+    if (hipEventRecord(ev.b, st) != hipSuccess || hipEventSynchronize(ev.b) != hipSuccess || hipGetLastError() != hipSuccess) return SV_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess || !(ms > 0.f)) return SV_EHIP;
+    *gbs = (double)bytes * reps / (ms * 1e-3) / 1e9;
+    return SV_OK;
+}

@@ -299,24 +299,39 @@ __global__ void select_kernel(SampleArgs a) {
     for (int i = acc + 1; i <= a.k; ++i) out[i] = -1;
 }
 
-// Move the kept chain's accepted entries to slots L+1 .. L+a (chain 0 already sits there).
+// Move the kept chain's accepted entries to slots L+1 .. L+a (chain 0 already sits there).  One work-group per
+// (request, layer).  In the tile layout of the cache a key's K entries of one head are head_dim/8 whole 16-byte
+// pieces (one per 8-wide slice of the head), moved as such with one index computation each; its V entries lie
+// one element apart per dimension (V is stored transposed, keys innermost) and move one by one.  Source slots
+// (>= L+1+k for a chain other than 0) and destination slots (<= L+k) never overlap.
 template <typename T>
-__global__ void compact_kernel(RollbackArgs r) {
+__global__ __launch_bounds__(256) void compact_kernel(RollbackArgs r) {
     const int b = blockIdx.x, layer = blockIdx.y;
     const int best = r.best_chain[b], acc = r.accepted_len[b];
-    if (best == 0 || acc == 0) return;
+    if (best <= 0 || best >= r.N || acc <= 0 || acc > r.k) return;
     const int seq = r.batch_seq[b];
     const int L = r.seq_len[seq];
     const int32_t* pages = r.page_table + (int64_t)seq * r.max_pages_per_seq;
     T* pool = reinterpret_cast<T*>(r.pool);
-    const int per = r.geom.n_kv_heads * r.geom.head_dim;
-    for (int e = threadIdx.x; e < acc * per; e += blockDim.x) {
-        const int i = e / per + 1, rem = e % per, h = rem / r.geom.head_dim, d = rem % r.geom.head_dim;
+    const int hd = r.geom.head_dim, H = r.geom.n_kv_heads;
+    constexpr int EPP = 16 / (int)sizeof(T);              // elements per 16-byte piece
+    const int ppk = hd / 8;                               // pieces of 8 consecutive dimensions per (key, head)
+    // K: 8 consecutive dimensions of one key are contiguous (16 bytes in bf16, two 16-byte pieces in fp32)
+    for (int e = threadIdx.x; e < acc * H * ppk; e += 256) {
+        const int i = e / (H * ppk) + 1, rem = e % (H * ppk), h = rem / ppk, d = (rem % ppk) * 8;
         const int src = L + 1 + best * r.k + (i - 1), dst = L + i;
-        const int sp = pages[src / r.geom.page_size], st = src % r.geom.page_size;
-        const int dp = pages[dst / r.geom.page_size], dt = dst % r.geom.page_size;
-        pool[kv_k_index(r.geom, layer, dp, h, dt, d)] = pool[kv_k_index(r.geom, layer, sp, h, st, d)];
-        pool[kv_v_index(r.geom, layer, dp, h, dt, d)] = pool[kv_v_index(r.geom, layer, sp, h, st, d)];
+        const int64_t si = kv_k_index(r.geom, layer, pages[src / r.geom.page_size], h, src % r.geom.page_size, d);
+        const int64_t di = kv_k_index(r.geom, layer, pages[dst / r.geom.page_size], h, dst % r.geom.page_size, d);
+#pragma unroll
+        for (int q = 0; q < 8 / EPP; ++q)
+            *reinterpret_cast<u32x4*>(pool + di + q * EPP) = *reinterpret_cast<const u32x4*>(pool + si + q * EPP);
+    }
+    // V: one element per (key, head, dimension)
+    for (int e = threadIdx.x; e < acc * H * hd; e += 256) {
+        const int i = e / (H * hd) + 1, rem = e % (H * hd), h = rem / hd, d = rem % hd;
+        const int src = L + 1 + best * r.k + (i - 1), dst = L + i;
+        pool[kv_v_index(r.geom, layer, pages[dst / r.geom.page_size], h, dst % r.geom.page_size, d)] =
+            pool[kv_v_index(r.geom, layer, pages[src / r.geom.page_size], h, src % r.geom.page_size, d)];
     }
 }
 
@@ -375,14 +390,14 @@ hipError_t sample_verify(const SampleArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t rollback(const RollbackArgs& r, hipStream_t st) {
+hipError_t rollback(const RollbackArgs& r, hipStream_t st, bool commit) {
     if (r.N > 1) {
         if (r.dtype == 1)
             hipLaunchKernelGGL(compact_kernel<bf16_t>, dim3(r.B, r.n_layers), dim3(256), 0, st, r);
         else
             hipLaunchKernelGGL(compact_kernel<float>, dim3(r.B, r.n_layers), dim3(256), 0, st, r);
     }
-    hipLaunchKernelGGL(commit_len_kernel, dim3((r.B + 63) / 64), dim3(64), 0, st, r);
+    if (commit) hipLaunchKernelGGL(commit_len_kernel, dim3((r.B + 63) / 64), dim3(64), 0, st, r);
     return hipGetLastError();
 }
 
