@@ -173,33 +173,8 @@ def random_case(B, N, k, V, seed, sigma_q=1.0, with_q=True):
 
 
 def oracle_sample(logits, drafts, q, u, verify_mode, sample_mode, temperature, draft_lens=None):
-    B, N, k = drafts.shape
-    V = logits.shape[-1]
-    per_chain = np.empty((B, N, k + 1, V))
-    for c in range(N):
-        per_chain[:, c, 0] = logits[:, 0]
-        per_chain[:, c, 1:] = logits[:, 1 + c * k: 1 + (c + 1) * k]
-    S = B * N
-    lens = None if draft_lens is None else np.repeat(draft_lens, N)
-    if verify_mode == OV.GREEDY:
-        v = OV.verify_greedy(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k), lens)
-    elif verify_mode == OV.MATCH:
-        v = OV.verify_match(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
-                            np.repeat(u[:, :1, :], N, axis=1).reshape(S, k + 1), np.repeat(np.arange(B), N),
-                            temperature, sample_mode, lens)
-    else:
-        v = OV.verify_stochastic(per_chain.reshape(S, k + 1, V), drafts.reshape(S, k),
-                                 None if q is None else q.numpy().reshape(S, k, V), u.reshape(S, k + 1),
-                                 np.arange(S, dtype=np.uint64), temperature, sample_mode, lens)
-    a = v.accepted.reshape(B, N)
-    best = np.argmax(a, axis=1)
-    out = np.full((B, k + 1), -1, dtype=np.int64)
-    for b in range(B):
-        ab = a[b, best[b]]
-        out[b, :ab] = drafts[b, best[b], :ab]
-        out[b, ab] = v.token.reshape(B, N)[b, best[b]]
-    margin = np.minimum(v.accept_margin, v.draw_margin).reshape(B, N).min(axis=1)
-    return a[np.arange(B), best], out, best, margin
+    from harness import decide
+    return decide(logits, drafts, None if q is None else q.numpy(), u, verify_mode, sample_mode, temperature, draft_lens)
 
 
 CASES = [
@@ -343,3 +318,60 @@ def test_sampler_rejects_draft_ids_outside_the_vocabulary(vmode, smode, with_q):
         if margin[b] >= 1e-5:
             assert ga[b] == a[b] and np.array_equal(gout[b], out[b]), (b, ga[b], a[b], gout[b], out[b])
     assert (a == bad_slot).sum() >= 2                             # some walks did reach the planted id
+
+
+@pytest.mark.parametrize("dtype,hd,N,k", [("bf16", 128, 3, 8), ("bf16", 128, 2, 3), ("fp32", 64, 3, 4), ("bf16", 128, 1, 4)])
+def test_rollback_moves_the_kept_chain_next_to_x0(dtype, hd, N, k):
+    """The rollback stage alone on given verdicts, against the oracle's rollback on the same cache contents:
+    lengths that put the moved entries across 32-key tiles and 64-key pages, every kept chain and accepted
+    length, a verdict that keeps chain 0 (nothing moves) and two that are out of range (nothing moves, nothing
+    is touched); afterwards every slot of every layer is compared bit for bit -- moved entries, entries that
+    had to stay, and the dead ones beyond."""
+    import paper_2511_16193_amd as P
+    hkv, layers = 2, 3
+    n = 1 + N * k
+    lengths = [0, 5, 30, 31, 56, 60, 63, 64, 100, 127, 1000]
+    B = len(lengths)
+    shape = W.Shape("rb", layers, 256, 2 * hkv, hkv, hd, 512, 2048, dtype=dtype)
+    spec = M.ModelSpec(**shape.model_fields())
+    wd = W.make_weights(shape, DEV)
+    ver = P.Verifier(shape.model_fields(), wd, max_batch=B, max_k=k, max_chains=N, max_seqs=B, page_size=64,
+                     num_pages=B * 18, max_pages_per_seq=18, verify_mode=0)
+    rng = np.random.default_rng(3)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    caches = []
+    for b, L in enumerate(lengths):
+        ver.seq_add(b, L + n)                                  # a pass has appended its n rows
+        c = M.SeqCache(spec, L + n)
+        for l in range(layers):
+            kk = torch.from_numpy(rng.standard_normal((L + n, hkv, hd)).astype(np.float32)).to(tdt)
+            vv = torch.from_numpy(rng.standard_normal((L + n, hkv, hd)).astype(np.float32)).to(tdt)
+            ver.kv_write(b, l, 0, kk.to(DEV), vv.to(DEV))
+            c.k[l][:] = kk.float().numpy()
+            c.v[l][:] = vv.float().numpy()
+        c.length = L
+        caches.append(c)
+    ver.seq_set_lens(list(range(B)), lengths)                  # live lengths back to before the pass
+    best = rng.integers(0, N, B).astype(np.int32)
+    acc = rng.integers(0, k + 1, B).astype(np.int32)
+    best[0], acc[0] = N - 1, k                                 # the longest move there is
+    best[1], acc[1] = 0, k                                     # chain 0 already sits in place
+    dev_best, dev_acc = best.copy(), acc.copy()
+    if N > 1:
+        dev_best[2], dev_acc[3] = N + 5, k + 7                 # out of range: must move nothing
+        best[2], acc[3] = 0, 0                                 # (what the oracle is told instead)
+        acc[2] = dev_acc[2]
+        best[3] = dev_best[3]
+    ver.op_rollback(list(range(B)), N, k, torch.from_numpy(dev_acc).to(DEV), torch.from_numpy(dev_best).to(DEV), commit=False)
+    torch.cuda.synchronize()
+    for b, L in enumerate(lengths):                            # (reading a length back would release the pages beyond it)
+        OV.rollback(caches[b], int(best[b]), int(acc[b]), k)
+        for l in range(layers):
+            kd, vd = ver.kv_read(b, l, 0, L + n)
+            assert np.array_equal(kd.float().cpu().numpy(), caches[b].k[l][:L + n]), (b, l)
+            assert np.array_equal(vd.float().cpu().numpy(), caches[b].v[l][:L + n]), (b, l)
+    # with commit the lengths advance by a + 1 (out-of-range verdicts aside, which the step never produces); without, not
+    ver.op_rollback(list(range(B)), N, k, torch.from_numpy(acc).to(DEV), torch.from_numpy(best).to(DEV), commit=False)
+    ver.op_rollback(list(range(B)), N, k, torch.from_numpy(acc).to(DEV), torch.from_numpy(best).to(DEV), commit=True)
+    assert [ver.seq_len(b) for b in range(B)] == [L + int(a) + 1 for L, a in zip(lengths, acc)]
+    ver.close()
