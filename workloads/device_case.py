@@ -22,7 +22,7 @@ from . import synth
 class DeviceCase:
     def __init__(self, shape: Shape, *, k: int | None = None, n_chains: int | None = None, page_size: int = 64,
                  verify_mode: int | None = None, sample_mode: int = 1, packed: bool = True, keep_row_major=True,
-                 device="cuda:0", log=None):
+                 max_chains: int | None = None, headroom_tokens: int = 0, device="cuda:0", log=None):
         from paper_2511_16193_amd import Verifier, pack_weights
         self.shape, self.device = shape, torch.device(device)
         self.k = shape.k if k is None else k
@@ -30,8 +30,9 @@ class DeviceCase:
         self.B = shape.batch
         self.log = log or (lambda *_: None)
         self.lengths = synth.make_prefix_lengths(shape)
-        n = 1 + self.N * self.k
-        headroom = n + self.k + 2
+        self.max_chains = max(self.N, max_chains or 1)       # the context may be sized for more chains than a step uses
+        n = 1 + self.max_chains * self.k
+        headroom = n + self.k + 2 + headroom_tokens            # headroom_tokens: room for steps that are not put back
         pages = [int((L + headroom + page_size - 1) // page_size) for L in self.lengths]
         self.log(f"weights for {shape.name} ...")
         self.weights = synth.make_weights(shape, self.device)           # row-major (what the oracle reads)
@@ -48,7 +49,7 @@ class DeviceCase:
             torch.cuda.empty_cache()
         self.ver = Verifier(shape.model_fields(), self.weights_dev, packed=packed_now,
                             max_batch=self.B, max_k=max(self.k, 1),
-                            max_chains=self.N, max_seqs=self.B, page_size=page_size, num_pages=sum(pages) + 4,
+                            max_chains=self.max_chains, max_seqs=self.B, page_size=page_size, num_pages=sum(pages) + 4,
                             max_pages_per_seq=max(pages) + 1,
                             verify_mode=shape.verify_mode if verify_mode is None else verify_mode,
                             sample_mode=sample_mode, temperature=1.0, device=device)
@@ -65,13 +66,19 @@ class DeviceCase:
         self.uniforms = torch.from_numpy(synth.make_uniforms((self.B, self.N, self.k + 1), shape.seed, "u")).to(self.device)
         self.drafts = None
         self.draft_probs = None
+        self.cur_lengths = [int(x) for x in self.lengths]      # the state reset() goes back to
 
     def kv_block(self, b: int, layer: int):
         """The synthetic cache contents of (request, layer), regenerated from the seed."""
         return synth.make_kv_block(self.shape, self.shape.seed, b, layer, int(self.lengths[b]), self.device)
 
     def reset(self):
-        self.ver.seq_set_lens(self.ids, [int(x) for x in self.lengths])
+        self.ver.seq_set_lens(self.ids, self.cur_lengths)
+
+    def commit(self, accepted_len):
+        """Make the state after a step (accepted_len: the step's output, read on the host) the one reset() goes
+        back to: consecutive steps, each on the rolled-back cache of the one before."""
+        self.cur_lengths = [L + int(a) + 1 for L, a in zip(self.cur_lengths, accepted_len)]
 
     def independent_drafts(self, sigma: float = 1.0):
         """Drafts sampled from q = softmax(sigma N(0,1)), unrelated to the target (random-weight targets are
@@ -81,9 +88,17 @@ class DeviceCase:
         d = synth.sample_from(q, self.shape.seed, "indep").to(torch.int32)
         self.drafts, self.draft_probs = d.contiguous(), q.contiguous()
 
-    def noisy_target_drafts(self, sigmas=None):
-        """The configuration's recipe (see module docstring)."""
+    def one_hot_drafts(self):
+        """Drafts without a distribution (what an n-gram or suffix-automaton drafter proposes): seeded token ids,
+        draft_probs = None, i.e. q is one-hot on the draft."""
+        self.independent_drafts(1.0)
+        self.draft_probs = None
+
+    def noisy_target_drafts(self, sigmas=None, x0=None):
+        """The configuration's recipe (see module docstring), drafted from the state reset() goes back to."""
         V, B, N, k = self.shape.vocab, self.B, self.N, self.k
+        if x0 is not None:
+            self.x0 = x0.to(device=self.device, dtype=torch.int32).contiguous()
         sigmas = list(sigmas if sigmas is not None else self.shape.draft_sigma)
         drafts = torch.empty((B, N, k), dtype=torch.int32, device=self.device)
         q = torch.empty((B, N, k, V), dtype=torch.float32, device=self.device)

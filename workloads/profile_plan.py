@@ -1,6 +1,6 @@
 """Profile the affine latency models of the paper's Section 4.1 on this GPU and run the plan search on them.
 
-    python -m paper_2511_16193_amd.profile_plan [--verifier cfg3] [--batches 8,16,32,64,128,256]
+    python -m workloads.profile_plan [--verifier cfg3] [--batches 8,16,32,64,128,256]
                                                 [--windows 1,2,4,8] [--p 0.8] [--B 256] [--json out.json]
 
 Verification time V_w(b): the library's verification step on the verifier shape (a workload configuration's
@@ -10,7 +10,7 @@ draft model.  Both are timed as whole steps, inputs resident, median of a few ru
 the points give V'_w, beta_w, D', alpha (sv_fit_affine); windows that were not measured are interpolated
 linearly between measured ones.  With one GPU for each role (g_d = g_v = 1, G = 2) Algorithm 1 reduces to the
 choice of the window; the script prints that plan, the whole TGS table, and the best window per acceptance rate.
-Needs the repository root on sys.path (it builds its inputs with the `workloads` package).
+Run from the repository root.
 """
 from __future__ import annotations
 

@@ -1,11 +1,11 @@
 """Time the prefill entry points on a workload configuration's model.
 
-    python -m paper_2511_16193_amd.profile_prefill [--config cfg2] [--prompts 64] [--tokens 512] [--rows 5,32]
+    python -m workloads.profile_prefill [--config cfg2] [--prompts 64] [--tokens 512] [--rows 5,32]
 
 For each `rows` value a verifier is set up whose steps hold that many rows per request (max_k = rows - 1), and
 `prompts` seeded prompts of `tokens` tokens are prefetched together with verify_prefill_batch (`rows` tokens of each
 per pass); then one prompt alone with verify_prefill (64-token chunks of a single sequence).  Prints one JSON
-line with tokens per second of each.  Needs the repository root on sys.path (inputs come from `workloads`).
+line with tokens per second of each.  Run from the repository root.
 """
 from __future__ import annotations
 
