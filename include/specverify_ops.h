@@ -53,6 +53,20 @@ int sv_op_sample(const float *logits, const int32_t *drafts, const float *draft_
                  float temperature, void *scratch, int32_t *accepted_len, int32_t *out_tokens,
                  int32_t *best_chain, void *stream);
 
+/* sv_op_sample for callers that cannot allocate device memory or bring a scratch buffer: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * sv_op_sample without `scratch`: the scratch lives in a static device array of the library (624 KiB, held on
+ * every GPU the library runs on until the process ends).  Limits: B * (1 + N * k) <= 4096 logits rows and
+ * B * N <= 4096 chains; beyond them SV_EINVAL and nothing is enqueued.  The call allocates nothing (no
+ * hipMalloc / hipFree, no allocating library routine); the caller still provides inputs and outputs.  All
+ * calls on one GPU share the one array, which keeps the previous call's contents (no field is read before the
+ * same call has written it, so nothing is cleared): calls that overlap on one GPU -- different streams,
+ * different threads -- race on it; calls on one stream are ordered and safe. */
+int sv_op_sample_static(const float *logits, const int32_t *drafts, const float *draft_probs, const float *uniforms,
+                        const int32_t *draft_lens, int B, int N, int k, int V, int verify_mode, int sample_mode,
+                        float temperature, int32_t *accepted_len, int32_t *out_tokens, int32_t *best_chain,
+                        void *stream);
+
 /* Verify attention alone (the part of parallel verification bound by HBM: every cached K/V byte is read
  * once for all n rows of a request).  For each listed sequence (HOST array seq_ids[B], live length L_b) the
  * n query rows q [B*n, n_q_heads, head_dim] (storage type) attend cache entries 0 .. L_b-1 and, of the

@@ -25,7 +25,7 @@ EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_prefill_batch", "verify_step",
-    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_op_layer", "sv_op_rollback", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
+    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_sample_static", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_op_layer", "sv_op_rollback", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
     "sv_profile_read", "sv_probe_mfma_bf16", "sv_probe_hbm_copy", "sv_probe_hbm_read",
     "sv_plan_accept_prob", "sv_plan_tau", "sv_plan_decoupled", "sv_plan_best_window", "sv_fit_affine",
 ]
@@ -107,6 +107,7 @@ def load_library() -> C.CDLL:
     lib.sv_op_sample_scratch_bytes.restype = C.c_size_t
     lib.sv_op_sample_scratch_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     lib.sv_op_sample.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 5
+    lib.sv_op_sample_static.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 4
     lib.sv_op_moe_scratch_bytes.restype = C.c_size_t
     lib.sv_op_moe_scratch_bytes.argtypes = [C.c_int] * 5
     lib.sv_op_moe_ffn.argtypes = [C.c_void_p] * 4 + [C.c_int] * 5 + [C.c_void_p, C.c_size_t] + [C.c_void_p] * 4
@@ -453,6 +454,22 @@ def op_sample(logits: torch.Tensor, drafts: torch.Tensor, draft_probs, uniforms,
                             _stream_ptr())
     if rc != 0:
         raise SvError(rc, "sv_op_sample")
+    return acc, toks, best
+
+
+def op_sample_static(logits: torch.Tensor, drafts: torch.Tensor, draft_probs, uniforms, acc: torch.Tensor,
+                     toks: torch.Tensor, best: torch.Tensor, *, verify_mode: int, sample_mode: int = SV_EXP_RACE,
+                     temperature: float = 1.0, draft_lens=None):
+    """sv_op_sample on the library's static scratch: the caller brings the outputs too (acc int32 [B], toks int32
+    [B,k+1], best int32 [B]), so that nothing at all is allocated between the call and its kernels."""
+    B, N, k = drafts.shape
+    V = logits.shape[-1]
+    assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.shape[1] == 1 + N * k
+    rc = lib().sv_op_sample_static(_ptr(logits), _ptr(drafts), _ptr(draft_probs), _ptr(uniforms), _ptr(draft_lens), B, N, k,
+                                   V, verify_mode, sample_mode, temperature, _ptr(acc), _ptr(toks), _ptr(best),
+                                   _stream_ptr())
+    if rc != 0:
+        raise SvError(rc, "sv_op_sample_static")
     return acc, toks, best
 
 

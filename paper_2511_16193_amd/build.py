@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecverify.so")
-SOURCES = ["gemm.hip", "elementwise.hip", "attention.hip", "sampler.hip", "moe.hip", "context.hip", "plan.hip", "probe.hip"]
+SOURCES = ["gemm.hip", "elementwise.hip", "attention.hip", "sampler.hip", "moe.hip", "context.hip", "plan.hip", "static_scratch.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-fvisibility=default",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
