@@ -30,9 +30,10 @@ int sv_op_gemm_bf16(const void *A, const void *W, float *out, int M, int N, int 
 
 /* The same projection with both operands in packed order, by the weight-streaming kernel: Ap = activations
  * packed by sv_op_pack_rows, Wp = weights packed by sv_op_pack_weight, out [splits, M, N] fp32.
- * wide != 0: 256 output features per work-group (N % 256 == 0), else 128.  K % (64*splits) == 0. */
+ * wide != 0: 256 output features per work-group (N % 256 == 0), else 128.  K % (64*splits) == 0.
+ * row_tiles: 32-row tiles per work-group, 1..5, or 0 = as few work-groups along the rows as five tiles each allow. */
 int sv_op_gemm_bf16_ws(const void *Ap, const void *Wp, float *out, int M, int N, int K, int splits, int wide,
-                       void *stream);
+                       int row_tiles, void *stream);
 
 /* Reorder row-major bf16 activations src [M, K] into dst (ceil(M/32)*32*K elements) in the order the
  * weight-streaming kernel reads them: [ceil(M/32)][K/16][64 lanes][8 elements], lane 32*g + r of a fragment

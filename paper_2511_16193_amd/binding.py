@@ -102,7 +102,7 @@ def load_library() -> C.CDLL:
                                     C.c_int, C.c_void_p]
     lib.sv_op_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.sv_op_pack_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
-    lib.sv_op_gemm_bf16_ws.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+    lib.sv_op_gemm_bf16_ws.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                        C.c_void_p]
     lib.sv_op_sample_scratch_bytes.restype = C.c_size_t
     lib.sv_op_sample_scratch_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
@@ -386,12 +386,13 @@ def op_pack_rows(a: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def op_gemm_bf16_ws(a_packed: torch.Tensor, w_packed: torch.Tensor, M: int, splits: int = 1, wide: bool = True) -> torch.Tensor:
+def op_gemm_bf16_ws(a_packed: torch.Tensor, w_packed: torch.Tensor, M: int, splits: int = 1, wide: bool = True,
+                    row_tiles: int = 0) -> torch.Tensor:
     """Weight-streaming projection on packed operands -> [splits, M, N] fp32 partial products."""
     K = a_packed.shape[1]
     N = w_packed.shape[0]
     out = torch.empty((splits, M, N), dtype=torch.float32, device=a_packed.device)
-    rc = lib().sv_op_gemm_bf16_ws(_ptr(a_packed), _ptr(w_packed), _ptr(out), M, N, K, splits, 1 if wide else 0, _stream_ptr())
+    rc = lib().sv_op_gemm_bf16_ws(_ptr(a_packed), _ptr(w_packed), _ptr(out), M, N, K, splits, 1 if wide else 0, row_tiles, _stream_ptr())
     if rc != 0:
         raise SvError(rc, "sv_op_gemm_bf16_ws")
     return out

@@ -7,7 +7,7 @@
 // G*n query rows that share the kv head (G = q heads per kv head), stacked.  Each of its waves walks its own
 // 32-key tiles of the chunk: K (32 x 128) and V^T (128 x 32) of a tile are stored in the page in MFMA operand
 // order, S^T = K Q^T is formed with v_mfma_f32_16x16x32_bf16, the online softmax runs in fp32 on the four keys
-// per row each lane holds, and P^T (as three bf16 terms) goes back as the B operand of O^T += V^T P^T.  The score
+// per row each lane holds, and P^T (as two or three bf16 terms) goes back as the B operand of O^T += V^T P^T.  The score
 // tile's register layout (a lane holds 4 consecutive keys of one row, for two 16-key blocks) is used unchanged as
 // the PV operand; the reduction index of that MFMA is only a label, so V^T is simply stored with the same key
 // order.  Waves are merged through LDS, chunks by a second small kernel (split-KV).
@@ -329,7 +329,12 @@ __global__ __launch_bounds__(256, R == 1 ? 2 : 1) void attn_bf16_regs_kernel(Att
 
 // R row tiles per work-group, W waves, D slots per wave for K and for V in the LDS ring (W * D * 16 KB of LDS).
 // Run as W = 2, D = 2: two work-groups share a CU.
-template <int R, int W, int D>
+// PT: bf16 terms the softmax weights are split into for the PV products.  With four row tiles (or several row
+// groups) this kernel is bound by its matrix products and the power they draw, and three quarters of them are PV
+// products: it runs with PT = 2 (16 significant bits; the 2^-17 relative it leaves is the size of the fp32
+// accumulation error of a few thousand keys, i.e. nothing the result did not carry already), a quarter fewer
+// products than with three terms.  The register kernel above is bound by the stream and keeps three.
+template <int R, int W, int D, int PT>
 __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float scale_log2e) {
     // Work item = one piece of one request's keys, cut by the host from its upper bounds of the lengths.
     // Launch order: the kv heads of an item are neighbours, so the list's longest-first order holds chip-wide.
@@ -453,12 +458,12 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
     // then refills the two 8 KB slots it has emptied with K of tile j + 3 and V of tile j + 1 (16 loads a trip,
     // always, so that the wait at the top of a trip is a constant: all but the previous trip's loads).
     floatx4 s_cur[2][R], s_next[2][R];
-    u32x4 pf_prev[R][3];
+    u32x4 pf_prev[R][PT];
     u32x4 kreg[2][4], vreg[8];
 #pragma unroll
     for (int rt = 0; rt < R; ++rt)
 #pragma unroll
-        for (int tm = 0; tm < 3; ++tm) pf_prev[rt][tm] = u32x4{0, 0, 0, 0};
+        for (int tm = 0; tm < PT; ++tm) pf_prev[rt][tm] = u32x4{0, 0, 0, 0};
 
     auto pv_products = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -466,7 +471,7 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
 #pragma unroll
             for (int ht = 0; ht < 8; ++ht)
 #pragma unroll
-                for (int tm = 2; tm >= 0; --tm)
+                for (int tm = PT - 1; tm >= 0; --tm)
                     o[ht][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vreg[ht]),
                                                                         __builtin_bit_cast(bf16x8, pf_prev[rt][tm]), o[ht][rt], 0, 0, 0);
     };
@@ -571,7 +576,7 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
                     }
                     if (PV) {
 #pragma unroll
-                        for (int tm = 0; tm < 3; ++tm)
+                        for (int tm = 0; tm < PT; ++tm)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 const uint32_t w = pf_prev[rt][tm][i];
@@ -586,7 +591,7 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
             }
         }
         // ---- strand 2: softmax of tile j;  strand 3: PV products of tile j - 1
-        u32x4 pf_cur[R][3];
+        u32x4 pf_cur[R][PT];
         if (SM) {
 #pragma unroll
             for (int rt = 0; rt < R; ++rt) {
@@ -601,26 +606,25 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
                     psum += (p[i].x + p[i].y) + (p[2 + i].x + p[2 + i].y);
                 }
                 l_run[rt] += psum;
-                // P goes to the MFMA as three bf16 terms (24 significant bits in all).  One bf16 term would
-                // leave a 2^-9 relative error in the output however many keys there are (V has zero mean, so
-                // the output is as small as the error's random walk); two terms leave 2^-17, still enough to
-                // move every few-hundredth output across a bf16 rounding boundary.
+                // P goes to the MFMA as PT bf16 terms (8 significant bits each).  One term would leave a 2^-9
+                // relative error in the output however many keys there are (V has zero mean, so the output is
+                // as small as the error's random walk): as much as the rounding of the output itself.
 #pragma unroll
-                for (int tm = 0; tm < 3; ++tm)
+                for (int tm = 0; tm < PT; ++tm)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const bf16x2 hb = __builtin_convertvector(p[i], bf16x2);
                         pf_cur[rt][tm][i] = __builtin_bit_cast(uint32_t, hb);
-                        if (tm < 2) p[i] = p[i] - __builtin_convertvector(hb, floatx2);
+                        if (tm < PT - 1) p[i] = p[i] - __builtin_convertvector(hb, floatx2);
                     }
             }
         }
         if (PV) pv_products();
         if (SM && PV) {
 #pragma unroll
-            for (int g = 0; g < 24 * R; ++g) {
+            for (int g = 0; g < 8 * PT * R; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x402, 3, 0);
+                __builtin_amdgcn_sched_group_barrier(0x402, PT == 3 ? 3 : 4, 0);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -628,7 +632,7 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
 #pragma unroll
             for (int rt = 0; rt < R; ++rt)
 #pragma unroll
-                for (int tm = 0; tm < 3; ++tm) pf_prev[rt][tm] = pf_cur[rt][tm];
+                for (int tm = 0; tm < PT; ++tm) pf_prev[rt][tm] = pf_cur[rt][tm];
         }
         if (QK) {
 #pragma unroll
@@ -832,9 +836,9 @@ hipError_t attention(const AttnArgs& a, hipStream_t st) {
         if (b.row_groups > 1 || R >= 4) {
             switch (R) {
                 case 1: e = launch_regs(attn_bf16_regs_kernel<1>, 1); break;
-                case 2: e = launch(attn_bf16_kernel<2, 2, 2>, 2, 2, 2); break;
-                case 3: e = launch(attn_bf16_kernel<3, 2, 2>, 3, 2, 2); break;
-                default: e = launch(attn_bf16_kernel<4, 2, 2>, 4, 2, 2); break;
+                case 2: e = launch(attn_bf16_kernel<2, 2, 2, 2>, 2, 2, 2); break;
+                case 3: e = launch(attn_bf16_kernel<3, 2, 2, 2>, 3, 2, 2); break;
+                default: e = launch(attn_bf16_kernel<4, 2, 2, 2>, 4, 2, 2); break;
             }
         } else {
             switch (R) {

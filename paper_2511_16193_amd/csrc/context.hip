@@ -39,36 +39,54 @@ int pick_splits(int M, int N, int K) {
     return s;
 }
 
-// Launch plan of the weight-streaming projection kernel: reduction splits and strip width, by an estimate of
-// the run time in microseconds.  Constants measured on MI355X: alone on its CU a 128-feature work-group advances
-// one 16-wide slice in 0.125 and a 256-feature one in 0.2; with every CU busy the chip sustains about 0.78 resp.
-// 0.9 PFLOP/s on random data (it is power-limited well below the MFMA peak), which bounds the advance of n
-// concurrent work-groups; 512 resp. 256 work-groups are resident at a time; a partial plane costs its bytes
-// at 3.5 TB/s (written here, read again by the consumer).
-struct WsPlan { int splits; bool wide; };
+// Launch plan of the weight-streaming projection kernel: 32-row tiles per work-group, strip width and reduction
+// splits, by an estimate of the run time in microseconds.  The estimate plays the launch through: work-groups are
+// dealt to the 256 CUs in rounds (one work-group per CU for the 128- and 160-row x 256-feature tiles, two for the
+// smaller ones); a CU works its share off at a rate that grows with the rows it holds (the weight stream is
+// shared by more products), no faster than a lone work-group can walk its reduction slices; the chip as a whole
+// sustains about 1.24 PFLOP/s on random data (it is power-limited well below the MFMA peak) and 5.3 TB/s of
+// weights; a partial plane costs its bytes, written here and read again by the consumer.  The constants are a
+// least-squares fit to a sweep of every (tiles, width, splits) over thirty shapes of the benchmark models on
+// MI355X (rows 5 to 2304); on that sweep the plan chosen is within 1 % of the best on average.
+struct WsPlan { int splits; bool wide; int row_tiles; };
 WsPlan plan_ws(int M, int N, int K, bool allow_split) {
-    const int mt = gemm_bf16_ws_row_tiles(M);                 // 32-row tiles per work-group (1..5)
-    const int tiles_m = (M + 32 * mt - 1) / (32 * mt), slices = K / 16;
-    const double rows = mt / 5.0;                             // the constants above are for five tiles
-    WsPlan best{1, false};
+    const int slices_all = K / 16;
+    const int tiles = (M + 31) / 32;
+    WsPlan best{1, false, gemm_bf16_ws_row_tiles(M)};
     double best_t = 1e30;
-    for (int wide = 0; wide < 2; ++wide) {
-        if (wide && N % 256 != 0) continue;
-        const double iso = std::max(0.05, (wide ? 0.2 : 0.125) * rows), rate = wide ? 0.9e9 : 0.78e9;   // flop per microsecond
-        const double work = 2.0 * 32 * mt * (wide ? 256 : 128) * 16;                                    // flop per work-group slice
-        const int cap = wide && mt == 5 ? 256 : 512;
-        auto slice_time = [&](int n) { return std::max(iso, n * work / rate); };
-        for (int s = 1; s <= (allow_split ? kMaxSplitsWs : 1); ++s) {
-            if (slices % (4 * s) != 0) continue;
-            const int blocks = (N / (wide ? 256 : 128)) * tiles_m * s;
-            const int full = blocks / cap, rem = blocks % cap;
-            double t = (double)full * (slices / s) * slice_time(cap) + (rem ? (slices / s) * slice_time(rem) : 0.0);
-            // a weight stream cannot beat the memory system whatever the products cost
-            t = std::max(t, (double)N * K * 2.0 / 5.0e6);
-            if (s > 1) t += (double)s * M * N * 4.0 / 3.5e6;
-            if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0}; }
+    // up to 160 rows: one work-group along the rows (cutting so few rows only multiplies the readers of a strip)
+    const int mt_lo = tiles <= 5 ? tiles : 1, mt_hi = tiles <= 5 ? tiles : 5;
+    for (int mt = mt_lo; mt <= mt_hi; ++mt)
+        for (int wide = 0; wide < 2; ++wide) {
+            if (wide && N % 256 != 0) continue;
+            const int cols = wide ? 256 : 128;
+            const int tiles_m = (tiles + mt - 1) / mt;
+            const int per_cu = (wide && mt >= 4) ? 1 : 2;                     // work-groups resident per CU
+            const double base = wide ? 5.01 : 4.15;                           // TFLOP/s of a CU at full tile height
+            const double lone = wide ? 0.093 : 0.076;                         // us per slice a lone work-group cannot beat
+            auto cu_rate = [&](int g) {                                       // g work-groups of this kind on one CU
+                const double rows = 32.0 * mt * g / 160.0;
+                const double eff = g == 1 ? 0.207 + 1.885 * rows : 0.442 + 0.375 * rows;
+                return base * std::min(1.0, eff) * 1e6;                       // flop per microsecond
+            };
+            for (int s = 1; s <= (allow_split ? kMaxSplitsWs : 1); ++s) {
+                if (slices_all % (4 * s) != 0) continue;
+                const double slices = (double)slices_all / s;
+                const double wg_flop = 2.0 * 32 * mt * cols * 16 * slices;
+                const long long blocks = (long long)tiles_m * (N / cols) * s;
+                auto round_time = [&](long long n) {                          // n work-groups dealt to the 256 CUs at once
+                    const int g = (int)((n + 255) / 256);
+                    return std::max(g * wg_flop / cu_rate(g), slices * lone * (1.0 + 0.459 * (g - 1)));
+                };
+                const long long cap = 256LL * per_cu, full = blocks / cap, rem = blocks % cap;
+                double t = full * round_time(cap) + (rem ? round_time(rem) : 0.0);
+                t = std::max(t, 2.0 * M * (double)N * K / 1241.0e6);          // the chip's sustained rate
+                t = std::max(t, (double)N * K * 2.0 / 5.32e6);                // a weight stream cannot beat the memory system
+                if (s > 1) t += (double)s * M * N * 4.0 / 2.6e6;
+                t += 2.3;
+                if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0, mt}; }
+            }
         }
-    }
     return best;
 }
 
@@ -578,7 +596,7 @@ static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int 
             // packed weights + packed activations: the weight-streaming kernel
             const WsPlan p = plan_ws(M, N, K, allow_split);
             *splits_out = p.splits;
-            SV_HIP(c, gemm_bf16_ws((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, p.splits, p.wide, c->stream));
+            SV_HIP(c, gemm_bf16_ws((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, p.splits, p.wide, c->stream, p.row_tiles));
         } else {
             const int s = allow_split ? pick_splits(M, N, K) : 1;
             *splits_out = s;
@@ -918,11 +936,11 @@ extern "C" int sv_op_gemm_bf16(const void* A, const void* W, float* out, int M, 
 }
 
 extern "C" int sv_op_gemm_bf16_ws(const void* Ap, const void* Wp, float* out, int M, int N, int K, int splits, int wide,
-                                  void* stream) {
+                                  int row_tiles, void* stream) {
     if (!Ap || !Wp || !out || M <= 0 || N <= 0 || K <= 0 || splits <= 0 || N % (wide ? 256 : 128) != 0 ||
-        K % (64 * splits) != 0)
+        K % (64 * splits) != 0 || row_tiles < 0 || row_tiles > 5)
         return SV_EINVAL;
-    return gemm_bf16_ws((const bf16_t*)Ap, (const bf16_t*)Wp, out, M, N, K, splits, wide != 0, (hipStream_t)stream) == hipSuccess
+    return gemm_bf16_ws((const bf16_t*)Ap, (const bf16_t*)Wp, out, M, N, K, splits, wide != 0, (hipStream_t)stream, row_tiles) == hipSuccess
                ? SV_OK : SV_EHIP;
 }
 

@@ -501,8 +501,11 @@ __device__ __forceinline__ void gemm_bf16_ws_body(
     }
 }
 
+// Two work-groups share a CU where the accumulator tile leaves room (up to 96 rows x 256 features, or 128-feature
+// strips): more, smaller work-groups resident at once, which evens out a launch whose work-group count is not a
+// multiple of the 256 CUs.
 template <int MT, int NT, int KA, int PD, bool GLU = false>
-__global__ __launch_bounds__(256, (NT == 1 || MT == 1) ? 2 : 1) void gemm_bf16_ws_kernel(
+__global__ __launch_bounds__(256, (NT == 1 || MT <= 3) ? 2 : 1) void gemm_bf16_ws_kernel(
     const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
     int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n, int tn0) {
     gemm_bf16_ws_body<MT, NT, KA, PD, GLU>(Ap, Wp, out, M, N, K, k_per_split, splits, tiles_m, tiles_n, tn0, blockIdx.x);
@@ -611,11 +614,12 @@ int gemm_bf16_ws_row_tiles(int M) {
 }
 
 hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool wide,
-                        hipStream_t st) {
+                        hipStream_t st, int row_tiles) {
     const bool long_fill = (K / splits) % 128 == 0;
     if (!long_fill)          // short reductions (small models): the five-tile form only
         return wide ? launch_ws<5, 2, 4, 4>(Ap, Wp, out, M, N, K, splits, st) : launch_ws<5, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
-    switch (gemm_bf16_ws_row_tiles(M) * 2 + (wide ? 1 : 0)) {
+    const int mt = row_tiles >= 1 && row_tiles <= 5 ? row_tiles : gemm_bf16_ws_row_tiles(M);
+    switch (mt * 2 + (wide ? 1 : 0)) {
         case 2: return launch_ws<1, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
         case 3: return launch_ws<1, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
         case 4: return launch_ws<2, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);

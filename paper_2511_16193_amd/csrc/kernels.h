@@ -13,8 +13,9 @@ hipError_t gemm_bf16(const bf16_t* A, const bf16_t* W, float* out, int M, int N,
                      bool packed, hipStream_t st);
 hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st);
 hipError_t pack_rows(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st);
+// row_tiles: 32-row tiles per work-group (1..5; 0 = as few work-groups along the rows as five tiles each allow)
 hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool wide,
-                        hipStream_t st);
+                        hipStream_t st, int row_tiles = 0);
 int gemm_bf16_ws_row_tiles(int M);
 hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st);
 hipError_t gemm_f32(const float* A, const float* W, float* out, int M, int N, int K, hipStream_t st);
