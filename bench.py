@@ -138,7 +138,6 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="requests per step (default: the configuration's)")
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--cpu-seqs", type=int, default=None, help="requests in the oracle sample (0 = skip; default per configuration)")
-    ap.add_argument("--gemm-variant", type=int, default=None)
     ap.add_argument("--no-graph", action="store_true", help="skip the extra pass that replays the steps from a HIP graph")
     ap.add_argument("--attn-chunk", type=int, default=None, help="keys per split-KV chunk (tuning)")
     ap.add_argument("--attn-max-row-tiles", type=int, default=None, help="16-row tiles per attention work-group (tuning)")
@@ -199,8 +198,6 @@ def main():
         args.cpu_seqs = 0
     case = DeviceCase(shape, k=args.k, verify_mode=vmode, keep_row_major={"device": True, "host": "host", "drop": False}[args.row_major],
                       max_chains=2, headroom_tokens=(k_eff + 1) * args.consecutive, log=log)
-    if args.gemm_variant is not None:
-        case.ver.set_option(P.SV_OPT_GEMM_VARIANT, args.gemm_variant)
     if args.attn_chunk is not None:
         case.ver.set_option(P.SV_OPT_ATTN_CHUNK_KEYS, args.attn_chunk)
     if args.attn_max_row_tiles is not None:

@@ -21,12 +21,10 @@ extern "C" {
  * throughput at large per-worker batch, Section 3 "Challenge #1"):
  *   out[s][m][n] = sum over k in split s of A[m][k] * W[n][k],   s = 0 .. splits-1
  * A [M,K] bf16, W [N,K] bf16, out [splits,M,N] fp32 (the consumer adds the splits).
- * N % 128 == 0, K % (64*splits) == 0.  variant selects the kernel and work-group tile (tokens x features):
- * 0: 128x128, 1: 64x128, 2: 256x128 staged through registers; 3: 160x256, 4: 160x128, 5: 128x256, 6: 128x128
- * loaded straight into LDS (3 and 5 need N % 256 == 0).  packed != 0: W is in sv_op_pack_weight order
- * (variants 3..6 only). */
+ * N % 128 == 0, K % (64*splits) == 0.  Row-major operands (the path of models whose weights are not packed);
+ * variant selects the work-group tile (tokens x features): 0: 128x128, 1: 64x128, 2: 256x128. */
 int sv_op_gemm_bf16(const void *A, const void *W, float *out, int M, int N, int K, int splits, int variant,
-                    int packed, void *stream);
+                    void *stream);
 
 /* The same projection with both operands in packed order, by the weight-streaming kernel: Ap = activations
  * packed by sv_op_pack_rows, Wp = weights packed by sv_op_pack_weight, out [splits, M, N] fp32.
@@ -137,7 +135,7 @@ int sv_probe_hbm_copy(const void *src, void *dst, size_t bytes, int reps, void *
 int sv_probe_hbm_read(const void *src, size_t bytes, int reps, void *sink, void *stream, double *gbs);
 
 /* Tuning / diagnostic knobs of a context.
- *   SV_OPT_GEMM_VARIANT  kernel / work-group tile of the bf16 projections (0..6; -1 = per shape, default)
+ *   SV_OPT_GEMM_VARIANT  work-group tile of the row-major bf16 projections (0..2; -1 = per shape, default)
  *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)
  *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for
  *   SV_OPT_ATTN_MAX_ROW_TILES  most 16-row tiles (1..4, default 4) one work-group of the bf16 attention takes;

@@ -99,7 +99,7 @@ def load_library() -> C.CDLL:
                                          C.POINTER(C.c_int32), C.c_void_p]
     lib.verify_step.argtypes = [C.c_void_p, C.POINTER(SvBatch), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(SvOut)]
     lib.sv_op_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
-                                    C.c_int, C.c_void_p]
+                                    C.c_void_p]
     lib.sv_op_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.sv_op_pack_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.sv_op_gemm_bf16_ws.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -427,13 +427,13 @@ def pack_weights(weights: dict) -> dict:
     return out
 
 
-def op_gemm_bf16(a: torch.Tensor, w: torch.Tensor, splits: int = 1, variant: int = 0, packed: bool = False) -> torch.Tensor:
-    """a [M,K] bf16, w [N,K] bf16 (row-major, or packed with packed=True) -> [splits, M, N] fp32 partial products."""
+def op_gemm_bf16(a: torch.Tensor, w: torch.Tensor, splits: int = 1, variant: int = 0) -> torch.Tensor:
+    """a [M,K] bf16, w [N,K] bf16, both row-major -> [splits, M, N] fp32 partial products."""
     assert a.dtype == torch.bfloat16 and w.dtype == torch.bfloat16 and a.is_contiguous() and w.is_contiguous()
     M, K = a.shape
     N = w.shape[0]
     out = torch.empty((splits, M, N), dtype=torch.float32, device=a.device)
-    rc = lib().sv_op_gemm_bf16(_ptr(a), _ptr(w), _ptr(out), M, N, K, splits, variant, 1 if packed else 0, _stream_ptr())
+    rc = lib().sv_op_gemm_bf16(_ptr(a), _ptr(w), _ptr(out), M, N, K, splits, variant, _stream_ptr())
     if rc != 0:
         raise SvError(rc, "sv_op_gemm_bf16")
     return out

@@ -579,14 +579,10 @@ static int stage_batch(sv_ctx* c, const int32_t* ids, int B, int extra) {
     return SV_OK;
 }
 
-// Work-group tile for a projection of M rows onto N features: the token extent (128 or 160) that wastes
-// fewer padded rows, 256 features wide when that still leaves enough work-groups.
-static int pick_variant(const sv_ctx* c, int M, int N) {
+// Work-group tile of the row-major projection kernel for M rows: 64, 128 or 256 tokens x 128 features.
+static int pick_variant(const sv_ctx* c, int M) {
     if (c->gemm_variant >= 0) return c->gemm_variant;
-    const int w128 = (M + 127) / 128 * 128, w160 = (M + 159) / 160 * 160;
-    const bool m160 = w160 < w128;
-    const bool wide = N % 256 == 0 && (N / 256) * ((M + (m160 ? 159 : 127)) / (m160 ? 160 : 128)) >= 256;
-    return m160 ? (wide ? 3 : 4) : (wide ? 5 : 6);
+    return M <= 64 ? 1 : M >= 512 ? 2 : 0;
 }
 
 static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int N, int K, int* splits_out, bool allow_split = true) {
@@ -600,7 +596,7 @@ static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int 
         } else {
             const int s = allow_split ? pick_splits(M, N, K) : 1;
             *splits_out = s;
-            SV_HIP(c, gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, pick_variant(c, M, N), false, c->stream));
+            SV_HIP(c, gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, s, pick_variant(c, M), c->stream));
         }
     } else {
         *splits_out = 1;
@@ -638,6 +634,31 @@ static int add_norm(sv_ctx* c, int T, int pending, const void* gain) {
     else
         SV_HIP(c, add_rmsnorm(h, c->at<float>(L.part), pending, gain, a_norm, m.dtype, T, m.d_model, m.rms_eps, c->packed, c->stream));
     return SV_OK;
+}
+
+// Row pitch of the split-KV partials for a pass of B requests with n rows each.  The buffers are sized for
+// max_batch requests with the rows of a verification step; a pass of fewer requests with more rows each (a prompt
+// prefilled in long chunks) may spread over the same memory with a larger pitch, up to the 256 stacked rows the MFMA
+// attention takes.
+static int attn_partial_pitch(const sv_ctx* c, int B, int n, int max_chunks) {
+    const Layout& L = c->lay;
+    const int G = c->model.n_q_heads / c->model.n_kv_heads;
+    const int need = attn_rows_pad(n, G);                 // padded stacked rows per kv head; 0: more than the kernels take
+    if (need == 0 || need <= L.rows_pad) return L.rows_pad;
+    const long long room = (long long)c->rt.max_batch * L.max_chunks * L.rows_pad / ((long long)B * std::max(1, max_chunks));
+    return room >= need ? need : L.rows_pad;
+}
+
+// Rows per request and pass when B prompts are prefilled together: what the workspace holds rows for, at most the 256
+// stacked rows per kv head of the MFMA attention, and no more than the split-KV partials have room for.
+static int prefill_width(const sv_ctx* c, int B) {
+    const Layout& L = c->lay;
+    const int G = c->model.n_q_heads / c->model.n_kv_heads;
+    int width = std::max(1, std::min(L.T / B, 256 / G));
+    while (width > 1 && attn_rows_pad(width, G) > L.rows_pad &&
+           (long long)c->rt.max_batch * L.rows_pad / B < attn_rows_pad(width, G))
+        --width;                                          // (the pitch is checked against the chunk count of the pass again)
+    return width;
 }
 
 // One decoder layer over the prepared rows.  On entry the residual stream h lacks `pending` (see add_norm) of
@@ -679,6 +700,7 @@ static int layer_rows(sv_ctx* c, int l, int B, int n, int k, int max_len_ub, int
         aa.n_work_dev = c->at<int32_t>(L.req_chunk) + 2 * c->rt.max_batch;
         aa.grid_items = B * L.max_chunks;
     }
+    aa.rows_pad = attn_partial_pitch(c, B, n, aa.max_chunks);
     {
         ProfScope prof(c, SV_PROF_ATTENTION);
         SV_HIP(c, attention(aa, st));
@@ -732,24 +754,8 @@ static int forward_rows(sv_ctx* c, int B, int n, int k, const int32_t* last_toke
 extern "C" int verify_prefill(sv_ctx* c, int32_t id, const int32_t* tokens, int32_t n, float* last_logits) {
     if (!c || !tokens) return SV_EINVAL;
     if (n <= 0) return c->fail(SV_EINVAL, "prefill of %d tokens", n);
-    if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
-    if (pages_for(c, c->seqs[id].len_ub + n) > c->rt.max_pages_per_seq)
-        return c->fail(SV_ENOPAGES, "sequence %d would exceed max_pages_per_seq", id);
-    const int chunk_max = std::min(c->lay.T, 64);
-    int done = 0;
-    while (done < n) {
-        const int cn = std::min(chunk_max, n - done);
-        SV_TRY(stage_batch(c, &id, 1, cn));
-        // a chunk is x0 plus one chain of cn-1 "drafts": causal visibility, every row kept
-        SV_TRY(forward_rows(c, 1, cn, cn - 1, tokens + done, tokens + done + 1, c->seqs[id].len_ub));
-        SV_HIP(c, add_len(c->at<int32_t>(c->lay.seq_len), c->at<int32_t>(c->lay.batch_seq), 1, cn, c->stream));
-        c->seqs[id].len_ub += cn;
-        done += cn;
-        if (done == n && last_logits)
-            SV_HIP(c, hipMemcpyAsync(last_logits, c->at<float>(c->lay.logits) + (size_t)(cn - 1) * c->model.vocab,
-                                     sizeof(float) * c->model.vocab, hipMemcpyDeviceToDevice, c->stream));
-    }
-    return SV_OK;
+    // a batch of one prompt: chunks of as many rows as the kernels take for a single request
+    return verify_prefill_batch(c, &id, 1, tokens, n, &n, last_logits);
 }
 
 // Prompts of several sequences at once.  Pass p covers tokens p*c .. p*c+c-1 of every prompt that is that long
@@ -763,16 +769,15 @@ extern "C" int verify_prefill_batch(sv_ctx* c, const int32_t* seq_ids, int32_t B
                                     const int32_t* n, float* last_logits) {
     if (!c || !seq_ids || !tokens || !n) return SV_EINVAL;
     if (B <= 0 || B > c->rt.max_batch || ld <= 0) return c->fail(SV_EINVAL, "prefill of %d prompts (limit %d), row pitch %d", B, c->rt.max_batch, ld);
+    const int width_max = prefill_width(c, B);
     for (int b = 0; b < B; ++b) {
         if (n[b] <= 0 || n[b] > ld) return c->fail(SV_EINVAL, "prompt %d has %d tokens (row pitch %d)", b, n[b], ld);
         if (b && n[b] > n[b - 1]) return c->fail(SV_EINVAL, "prompts must come longest first (prompt %d: %d after %d)", b, n[b], n[b - 1]);
         const int id = seq_ids[b];
         if (id < 0 || id >= c->rt.max_seqs || !c->seqs[id].live) return c->fail(SV_ENOSEQ, "sequence id %d not live", id);
-        if (pages_for(c, c->seqs[id].len_ub + n[b] + c->lay.T / c->rt.max_batch) > c->rt.max_pages_per_seq)
+        if (pages_for(c, c->seqs[id].len_ub + n[b] + width_max) > c->rt.max_pages_per_seq)     // the last pass may carry padding rows
             return c->fail(SV_ENOPAGES, "sequence %d would exceed max_pages_per_seq", id);
     }
-    const int G = c->model.n_q_heads / c->model.n_kv_heads;
-    const int width_max = std::max(1, std::min(c->lay.T / c->rt.max_batch, 256 / G));
     int32_t* len_dev = c->at<int32_t>(c->lay.chain_acc);          // free outside a verification step
     {   // the lengths travel through a slot of the pinned staging ring, like a batch's ids
         const int slot = c->ring_pos;
@@ -927,11 +932,9 @@ extern "C" int verify_step(sv_ctx* c, const sv_batch* bt, const int32_t* drafts,
 // -------------------------------------------------- single-operation entry points ---
 
 extern "C" int sv_op_gemm_bf16(const void* A, const void* W, float* out, int M, int N, int K, int splits, int variant,
-                               int packed, void* stream) {
-    if (!A || !W || !out || M <= 0 || !gemm_bf16_shape_ok(N, K, splits) || !gemm_bf16_variant_ok(variant, N) ||
-        (packed && variant < 3))
-        return SV_EINVAL;
-    return gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, splits, variant, packed != 0, (hipStream_t)stream) ==
+                               void* stream) {
+    if (!A || !W || !out || M <= 0 || !gemm_bf16_shape_ok(N, K, splits) || !gemm_bf16_variant_ok(variant, N)) return SV_EINVAL;
+    return gemm_bf16((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, splits, variant, (hipStream_t)stream) ==
                    hipSuccess ? SV_OK : SV_EHIP;
 }
 
@@ -1051,6 +1054,7 @@ extern "C" int sv_op_attention(sv_ctx* c, const int32_t* seq_ids, int B, int n, 
     aa.force_generic = c->attn_generic; aa.min_row_tiles = c->attn_min_rt; aa.max_row_tiles = c->attn_max_rt;
     aa.max_chunks = std::min(c->lay.max_chunks, (max_ub + n + c->attn_chunk - 1) / c->attn_chunk);
     aa.n_work_dev = nullptr; aa.grid_items = 0;
+    aa.rows_pad = attn_partial_pitch(c, B, n, aa.max_chunks);
     SV_HIP(c, attention(aa, c->stream));
     return SV_OK;
 }
@@ -1155,7 +1159,7 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
     drop_graphs(c);                                       // captured launches carry the options they were made with
     switch (option) {
         case SV_OPT_GEMM_VARIANT:
-            if (value < -1 || value > 6)
+            if (value < -1 || value > 2)
                 return c->fail(SV_EINVAL, "gemm variant %d", value);
             c->gemm_variant = value;
             return SV_OK;

@@ -131,160 +131,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(
     }
 }
 
-// ---- second bf16 kernel: v_mfma_f32_32x32x16_bf16, operand tiles loaded from global memory straight
-// into LDS (global_load_lds, 16 bytes per lane) in MFMA fragment order, through a ring of NS stages.
-//
-// Why 32x32x16: measured on MI355X, one wave per SIMD issuing independent 16x16x32 MFMAs back to back
-// reaches 1.34 PFLOP/s over the chip, the 32x32x16 form 2.41 PFLOP/s; a kernel whose accumulators leave
-// room for one wave per SIMD only must use the larger form.
-//
-// A fragment is the 1 KB a wave feeds to one MFMA operand: lane 32*g + r holds row r (of 32), elements
-// 8*g .. 8*g+7 of a 16-wide k slice.  A direct-to-LDS load writes lane l's 16 bytes at (base + 16*l), so
-// if lane 32*g + r fetches exactly that piece of global memory, the LDS image of the fragment is what
-// ds_read_b128 at (base + 16*lane) hands to the MFMA: no VGPR staging, no ds_write, no padding, no
-// bank conflicts.  The work-group is 4 waves side by side along the output features; a wave owns all
-// MT 32-token tiles x NT 32-feature tiles of its strip, so the activation fragments (the smaller operand)
-// are the ones re-read by every wave.
-// Ordering uses bare s_barrier + explicit vmcnt waits: the fence of __syncthreads() would drain the
-// loads of the stages still in flight.
-#define SV_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
-// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all-ones = no
-// wait).  The builtin, unlike inline assembly, is seen by the compiler's own wait-count bookkeeping.
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
-
-// With PACKED the weight matrix is stored fragment by fragment (see pack_weight_kernel): the stream a
-// work-group reads along k is contiguous in memory (4 KB per 128 output features per 16-wide k slice)
-// instead of 32-byte pieces 2*K bytes apart.
-template <int MT, int NT, int NS, bool PACKED>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_dma_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, float* __restrict__ out,
-    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n) {
-    constexpr int BM = 32 * MT, BN = 128 * NT;            // tokens x output features per work-group
-    constexpr int KS = BK / 16;                           // 16-wide k slices per stage
-    constexpr int FA = MT * KS, FW = 4 * NT * KS;         // fragments per stage
-    constexpr int FS = FA + FW;
-    static_assert(FS % 4 == 0, "fragments per stage must split evenly over 4 waves");
-    constexpr int LPW = FS / 4;                           // direct loads per wave per stage
-    constexpr int STAGE_BYTES = FS * 1024;
-    static_assert((NS - 1) * LPW < 64, "vmcnt range");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-    const int nblk = tiles_m * tiles_n * splits;
-    int logical = xcd_remap(blockIdx.x, nblk);
-    const int tm = logical % tiles_m;
-    logical /= tiles_m;
-    const int sp = logical % splits;
-    const int tn = logical / splits;
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int kbeg = sp * k_per_split;
-    const int nk = k_per_split / BK;
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int l32 = lane & 31, lg = lane >> 5;
-
-    // per-lane global source of each fragment this wave loads; fragment f of a stage:
-    //   f < FA : activation tile f / KS, k slice f % KS;   else weight tile (f - FA) / KS, k slice (f - FA) % KS
-    const bf16_t* src[LPW];
-    int step[LPW];                                        // elements between consecutive stages
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int f = wave + 4 * i;
-        if (f < FA) {
-            int row = m0 + (f / KS) * 32 + l32;
-            row = row < M ? row : M - 1;
-            src[i] = A + (int64_t)row * K + kbeg + (f % KS) * 16 + lg * 8;
-            step[i] = BK;
-        } else if (PACKED) {
-            const int fw = f - FA, nt = n0 / 32 + fw / KS;     // 32-row tile of W
-            src[i] = W + (((int64_t)(nt >> 2) * (K / 16) + (kbeg / 16 + fw % KS)) * 4 + (nt & 3)) * 512 + lane * 8;
-            step[i] = KS * 4 * 512;
-        } else {
-            const int fw = f - FA;
-            src[i] = W + (int64_t)(n0 + (fw / KS) * 32 + l32) * K + kbeg + (fw % KS) * 16 + lg * 8;
-            step[i] = BK;
-        }
-    }
-    auto issue = [&](int kt) {
-        unsigned char* base = smem + (kt % NS) * STAGE_BYTES + wave * 1024;
-#pragma unroll
-        for (int i = 0; i < LPW; ++i)
-            __builtin_amdgcn_global_load_lds((const void*)(src[i] + (int64_t)kt * step[i]), SV_LDS_PTR(base + i * 4096), 16, 0, 0);
-    };
-
-    floatx16 acc[NT][MT];
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-#pragma unroll
-        for (int j = 0; j < MT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    // Per stage: wait for its loads, barrier, refill the buffer consumed one stage ago, then walk the KS
-    // slices with the next slice's fragment reads issued right after the current slice's first MFMA, so
-    // that they complete under the remaining MFMAs.  Scheduling barriers pin that order (left alone, the
-    // compiler sinks every read next to its use and exposes the LDS latency each time).
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < nk) issue(s);
-
-    for (int kt = 0; kt < nk; ++kt) {
-        // stage kt has landed once at most the loads of the NS-2 younger stages are outstanding
-        if (kt + NS - 2 < nk) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        if (kt + NS - 1 < nk) issue(kt + NS - 1);         // refills the buffer every wave left before the barrier
-        const unsigned char* st = smem + (kt % NS) * STAGE_BYTES + lane * 16;
-        bf16x8 af[2][MT], wf[2][NT];
-        auto read_slice = [&](int ks, int buf) {
-#pragma unroll
-            for (int j = 0; j < MT; ++j) af[buf][j] = *reinterpret_cast<const bf16x8*>(st + (j * KS + ks) * 1024);
-#pragma unroll
-            for (int i = 0; i < NT; ++i)
-                wf[buf][i] = *reinterpret_cast<const bf16x8*>(st + (FA + ((wave * NT + i) * KS + ks)) * 1024);
-        };
-        read_slice(0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int b = ks & 1;
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][0], af[b][0], acc[0][0], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (ks + 1 < KS) read_slice(ks + 1, b ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < NT; ++i)
-#pragma unroll
-                for (int j = 0; j < MT; ++j)
-                    if (i + j > 0)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][i], af[b][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-
-    // lane holds, per (i, j) and register e: feature n0 + (wave*NT+i)*32 + 8*(e/4) + 4*lg + e%4, token m0 + j*32 + l32
-    float* dst = out + (int64_t)sp * M * N;
-#pragma unroll
-    for (int j = 0; j < MT; ++j) {
-        const int m = m0 + j * 32 + l32;
-        if (m < M) {
-#pragma unroll
-            for (int i = 0; i < NT; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + (wave * NT + i) * 32 + 8 * q + 4 * lg;
-                    *reinterpret_cast<floatx4*>(dst + (int64_t)m * N + n) =
-                        floatx4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                }
-        }
-    }
-}
-
-// ---- third bf16 kernel: weight streaming.  For the few hundred rows of a verification step the
+// ---- second bf16 kernel: weight streaming (v_mfma_f32_32x32x16_bf16; one wave per SIMD issuing independent
+// 16x16x32 MFMAs reaches 1.34 PFLOP/s over the chip, the 32x32x16 form 2.41: a kernel whose accumulators leave room
+// for one wave per SIMD only must use the larger form).  For the few hundred rows of a verification step the
 // projections sit on the ridge between HBM and MFMA, and what matters is that the weights stream at
 // memory speed.  A wave owns a strip of NT 32-feature tiles and loads ITS weight fragments (packed
 // order: one contiguous 1 KB per fragment) straight from global memory into the registers the MFMA
@@ -706,56 +557,17 @@ hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t
     return hipGetLastError();
 }
 
-template <int MT, int NT, int NS, bool PACKED>
-static hipError_t launch_dma(const bf16_t* A, const bf16_t* W, float* out, int M, int N, int K, int splits,
-                             hipStream_t st) {
-    constexpr int BM = 32 * MT, BN = 128 * NT;
-    if (N % BN != 0) return hipErrorInvalidValue;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-    const size_t lds = (size_t)NS * ((MT + 4 * NT) * (BK / 16)) * 1024;
-    auto kern = gemm_bf16_dma_kernel<MT, NT, NS, PACKED>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(256), lds, st, A, W, out, M, N, K, K / splits,
-                       splits, tiles_m, tiles_n);
-    return hipGetLastError();
-}
-
-int gemm_bf16_variant_ok(int variant, int N) {
-    switch (variant) {
-        case 0: case 1: case 2: case 4: case 6: return N % 128 == 0;
-        case 3: case 5: return N % 256 == 0;
-        default: return 0;
-    }
-}
+int gemm_bf16_variant_ok(int variant, int N) { return variant >= 0 && variant <= 2 && N % 128 == 0; }
 
 int gemm_bf16_shape_ok(int N, int K, int splits) {
     return N > 0 && K > 0 && splits > 0 && N % 128 == 0 && K % (BK * splits) == 0;
 }
 
 hipError_t gemm_bf16(const bf16_t* A, const bf16_t* W, float* out, int M, int N, int K, int splits, int variant,
-                     bool packed, hipStream_t st) {
-    if (packed) {
-        switch (variant) {
-            case 3: return launch_dma<5, 2, 3, true>(A, W, out, M, N, K, splits, st);
-            case 4: return launch_dma<5, 1, 4, true>(A, W, out, M, N, K, splits, st);
-            case 5: return launch_dma<4, 2, 3, true>(A, W, out, M, N, K, splits, st);
-            case 6: return launch_dma<4, 1, 4, true>(A, W, out, M, N, K, splits, st);
-            default: return hipErrorInvalidValue;           // the LDS-staged kernel reads row-major weights only
-        }
-    }
+                     hipStream_t st) {
     switch (variant) {
         case 1: return launch_bf16<2, 4, 2, 2>(A, W, out, M, N, K, splits, st);    // 64 x 128
         case 2: return launch_bf16<4, 4, 4, 2>(A, W, out, M, N, K, splits, st);    // 256 x 128, 8 waves
-        case 3: return launch_dma<5, 2, 3, false>(A, W, out, M, N, K, splits, st);  // 160 x 256, direct-to-LDS, 3 stages
-        case 4: return launch_dma<5, 1, 4, false>(A, W, out, M, N, K, splits, st);  // 160 x 128, 4 stages
-        case 5: return launch_dma<4, 2, 3, false>(A, W, out, M, N, K, splits, st);  // 128 x 256
-        case 6: return launch_dma<4, 1, 4, false>(A, W, out, M, N, K, splits, st);  // 128 x 128, 4 stages
         default: return launch_bf16<4, 4, 2, 2>(A, W, out, M, N, K, splits, st);   // 128 x 128
     }
 }

@@ -10,7 +10,7 @@ namespace sv {
 int gemm_bf16_shape_ok(int N, int K, int splits);
 int gemm_bf16_variant_ok(int variant, int N);
 hipError_t gemm_bf16(const bf16_t* A, const bf16_t* W, float* out, int M, int N, int K, int splits, int variant,
-                     bool packed, hipStream_t st);
+                     hipStream_t st);
 hipError_t pack_weight(const bf16_t* src, bf16_t* dst, int N, int K, hipStream_t st);
 hipError_t pack_rows(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st);
 // row_tiles: 32-row tiles per work-group (1..5; 0 = as few work-groups along the rows as five tiles each allow)

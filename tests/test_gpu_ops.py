@@ -16,27 +16,21 @@ def bf16_cpu(shape, std, seed):
     return (torch.randn(shape, generator=g) * std).to(torch.bfloat16)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("M_,N,K,splits", [(320, 512, 1024, 1), (37, 256, 512, 4), (129, 128, 64, 1), (1, 384, 2048, 8),
                                            (700, 640, 448, 1), (321, 768, 3584, 2), (320, 1024, 192, 1)])
 def test_gemm_bf16_matches_float64_product(variant, M_, N, K, splits):
-    """Several tiles plus a ragged last row tile; every split count; the reduction in float64 on the
-    same bf16 inputs is the reference.  fp32 accumulation of K <= 2048 products of magnitude ~0.02:
-    absolute error far below 1e-4."""
-    from paper_2511_16193_amd import op_gemm_bf16, op_pack_weight
-    if K % (64 * splits) or (variant in (3, 5) and N % 256):
-        pytest.skip("shape not covered by this tile")
+    """The row-major projection kernel: several tiles plus a ragged last row tile; every split count; the
+    reduction in float64 on the same bf16 inputs is the reference.  fp32 accumulation of K <= 3584 products of
+    magnitude ~0.02: absolute error far below 1e-4."""
+    from paper_2511_16193_amd import op_gemm_bf16
     a = bf16_cpu((M_, K), 1.0, 1)
     w = bf16_cpu((N, K), 0.02, 2)
     want = M.matmul_wt(a.float().numpy().astype(np.float64), w.float().numpy())
-    for packed in ([False, True] if variant >= 3 else [False]):
-        wd = w.to(DEV)
-        if packed:                      # weights reordered into the streaming order of the direct-to-LDS kernel
-            wd = op_pack_weight(wd)
-        got = op_gemm_bf16(a.to(DEV), wd, splits=splits, variant=variant, packed=packed)
-        torch.cuda.synchronize()
-        got = got.cpu().numpy().astype(np.float64).sum(axis=0)
-        assert np.max(np.abs(got - want)) < 1e-4, packed
+    got = op_gemm_bf16(a.to(DEV), w.to(DEV), splits=splits, variant=variant)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64).sum(axis=0)
+    assert np.max(np.abs(got - want)) < 1e-4
 
 
 @pytest.mark.parametrize("M_,N,K,splits,wide", [(320, 512, 1024, 1, True), (37, 256, 512, 4, True), (129, 128, 64, 1, False),
@@ -52,10 +46,12 @@ def test_gemm_weight_streaming_matches_float64_product(M_, N, K, splits, wide):
     a = bf16_cpu((M_, K), 1.0, 1)
     w = bf16_cpu((N, K), 0.02, 2)
     want = M.matmul_wt(a.float().numpy().astype(np.float64), w.float().numpy())
-    got = op_gemm_bf16_ws(op_pack_rows(a.to(DEV)), op_pack_weight(w.to(DEV)), M_, splits=splits, wide=wide)
-    torch.cuda.synchronize()
-    got = got.cpu().numpy().astype(np.float64).sum(axis=0)
-    assert np.max(np.abs(got - want)) < 1e-4
+    ap, wp = op_pack_rows(a.to(DEV)), op_pack_weight(w.to(DEV))
+    for row_tiles in (0, 1, 2, 3, 4, 5):              # 0: the default choice; 1..5: 32-row tiles per work-group, as the plan may pick
+        got = op_gemm_bf16_ws(ap, wp, M_, splits=splits, wide=wide, row_tiles=row_tiles)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy().astype(np.float64).sum(axis=0)
+        assert np.max(np.abs(got - want)) < 1e-4, row_tiles
 
 
 @pytest.mark.parametrize("k,n_chains,group", [(0, 1, 7), (1, 1, 7), (2, 1, 7), (4, 1, 7), (8, 1, 7), (4, 1, 8), (3, 3, 4),
