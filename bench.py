@@ -409,7 +409,7 @@ def main():
                "bytes_per_step": sampler_bytes_per_step(shape, B, N, k)}
 
     if args.calibrate_copy:
-        P.probe_copy(1 << 30, 1)                           # two dispatches of probe_copy_kernel, 1 GiB read + 1 GiB written each
+        P.probe_copy(1 << 30, 1)                           # ten dispatches of probe_copy_kernel, 1 GiB read + 1 GiB written each
 
     cpu = None
     if args.cpu_seqs > 0 and k > 0 and case.weights is not None:

@@ -33,6 +33,11 @@ int sv_op_gemm_bf16(const void *A, const void *W, float *out, int M, int N, int 
 int sv_op_gemm_bf16_ws(const void *Ap, const void *Wp, float *out, int M, int N, int K, int splits, int wide,
                        int row_tiles, void *stream);
 
+/* The launch shape verify_step gives the weight-streaming projection of M rows onto N features over K inputs
+ * (HOST pointers out: reduction splits, 256- or 128-feature strips, 32-row tiles per work-group).  Host arithmetic
+ * only.  N % 128 == 0, K % 64 == 0. */
+int sv_op_gemm_plan(int M, int N, int K, int *splits, int *wide, int *row_tiles);
+
 /* Reorder row-major bf16 activations src [M, K] into dst (ceil(M/32)*32*K elements) in the order the
  * weight-streaming kernel reads them: [ceil(M/32)][K/16][64 lanes][8 elements], lane 32*g + r of a fragment
  * holding row r of the 32-row tile, elements 8*g .. 8*g+7 of the 16-wide k slice; padding rows are zero. */
@@ -125,11 +130,11 @@ int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launch
  *   v_mfma_f32_32x32x16_bf16 on operands held in registers (read once from `operands`, at least 256*256*128
  *   bytes: random bf16 values give the rate on real data, zeros the unthrottled one); `sink` takes 65536 floats;
  *   *tflops (HOST) = achieved dense bf16 rate.
- * sv_probe_hbm_copy: `reps` plain copies of `bytes` (a multiple of 16, at least 1 MiB, both buffers 16-byte
- *   aligned, choose it far larger than the caches); *gbs_each_way (HOST) = bytes copied per second in GB/s, i.e.
- *   that much read and as much written.
- * sv_probe_hbm_read: `reps` plain read-only passes over `bytes` (same constraints); `sink` takes 4 bytes;
- *   *gbs (HOST) = bytes read per second in GB/s. */
+ * sv_probe_hbm_copy: plain copies of `bytes` (a multiple of 16, at least 1 MiB, both buffers 16-byte aligned, choose
+ *   it far larger than the caches), `reps` of them (after a warm-up) for each of five grid sizes;
+ *   *gbs_each_way (HOST) = bytes copied per second in GB/s at the best grid, i.e. that much read and as much written.
+ * sv_probe_hbm_read: the same for plain read-only passes over `bytes`; `sink` takes 4 bytes;
+ *   *gbs (HOST) = bytes read per second in GB/s at the best grid. */
 int sv_probe_mfma_bf16(const void *operands, size_t operand_bytes, float *sink, int iters, void *stream, double *tflops);
 int sv_probe_hbm_copy(const void *src, void *dst, size_t bytes, int reps, void *stream, double *gbs_each_way);
 int sv_probe_hbm_read(const void *src, size_t bytes, int reps, void *sink, void *stream, double *gbs);

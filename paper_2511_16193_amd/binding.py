@@ -25,7 +25,7 @@ EXPORTS = [
     "verify_kv_pool_bytes", "verify_workspace_bytes", "verify_init", "verify_destroy", "verify_last_error",
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_prefill_batch", "verify_step",
-    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_sample_static", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_op_layer", "sv_op_rollback", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
+    "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_gemm_plan", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_sample_static", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_op_layer", "sv_op_rollback", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
     "sv_profile_read", "sv_probe_mfma_bf16", "sv_probe_hbm_copy", "sv_probe_hbm_read",
     "sv_plan_accept_prob", "sv_plan_tau", "sv_plan_decoupled", "sv_plan_best_window", "sv_fit_affine",
 ]
@@ -104,6 +104,7 @@ def load_library() -> C.CDLL:
     lib.sv_op_pack_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.sv_op_gemm_bf16_ws.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                        C.c_void_p]
+    lib.sv_op_gemm_plan.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.sv_op_sample_scratch_bytes.restype = C.c_size_t
     lib.sv_op_sample_scratch_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     lib.sv_op_sample.argtypes = [C.c_void_p] * 5 + [C.c_int] * 6 + [C.c_float] + [C.c_void_p] * 5
@@ -396,6 +397,15 @@ def op_gemm_bf16_ws(a_packed: torch.Tensor, w_packed: torch.Tensor, M: int, spli
     if rc != 0:
         raise SvError(rc, "sv_op_gemm_bf16_ws")
     return out
+
+
+def op_gemm_plan(M: int, N: int, K: int) -> dict:
+    """The launch shape the step would give this projection: {"splits", "wide", "row_tiles"}."""
+    s, w, t = C.c_int(), C.c_int(), C.c_int()
+    rc = lib().sv_op_gemm_plan(M, N, K, C.byref(s), C.byref(w), C.byref(t))
+    if rc != 0:
+        raise SvError(rc, "sv_op_gemm_plan")
+    return {"splits": s.value, "wide": bool(w.value), "row_tiles": t.value}
 
 
 def op_moe_ffn(a: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_down: torch.Tensor, top_k: int):

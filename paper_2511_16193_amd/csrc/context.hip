@@ -44,10 +44,10 @@ int pick_splits(int M, int N, int K) {
 // dealt to the 256 CUs in rounds (one work-group per CU for the 128- and 160-row x 256-feature tiles, two for the
 // smaller ones); a CU works its share off at a rate that grows with the rows it holds (the weight stream is
 // shared by more products), no faster than a lone work-group can walk its reduction slices; the chip as a whole
-// sustains about 1.24 PFLOP/s on random data (it is power-limited well below the MFMA peak) and 5.3 TB/s of
+// sustains about 1.2 PFLOP/s on random data (it is power-limited well below the MFMA peak) and 5 TB/s of
 // weights; a partial plane costs its bytes, written here and read again by the consumer.  The constants are a
-// least-squares fit to a sweep of every (tiles, width, splits) over thirty shapes of the benchmark models on
-// MI355X (rows 5 to 2304); on that sweep the plan chosen is within 1 % of the best on average.
+// fit to a sweep of every (tiles, width, splits) over thirty shapes of the benchmark models on MI355X (rows 5 to
+// 2304); on that sweep the plan chosen is within 0.3 % of the best on average and 4.5 % at worst.
 struct WsPlan { int splits; bool wide; int row_tiles; };
 WsPlan plan_ws(int M, int N, int K, bool allow_split) {
     const int slices_all = K / 16;
@@ -62,27 +62,26 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split) {
             const int cols = wide ? 256 : 128;
             const int tiles_m = (tiles + mt - 1) / mt;
             const int per_cu = (wide && mt >= 4) ? 1 : 2;                     // work-groups resident per CU
-            const double base = wide ? 5.01 : 4.15;                           // TFLOP/s of a CU at full tile height
-            const double lone = wide ? 0.093 : 0.076;                         // us per slice a lone work-group cannot beat
-            auto cu_rate = [&](int g) {                                       // g work-groups of this kind on one CU
-                const double rows = 32.0 * mt * g / 160.0;
-                const double eff = g == 1 ? 0.207 + 1.885 * rows : 0.442 + 0.375 * rows;
-                return base * std::min(1.0, eff) * 1e6;                       // flop per microsecond
-            };
+            const double base = wide ? 5.19 : 4.14;                           // TFLOP/s of a CU at full tile height
+            const double lone = wide ? 0.0883 : 0.0683;                       // us per slice a lone work-group cannot beat
+            // share of that rate a CU reaches with one resp. two work-groups of mt tiles
+            static const double kOne[6] = {0, 0.56, 0.97, 0.94, 0.93, 0.98}, kTwo[6] = {0, 0.58, 0.82, 0.90, 0.96, 0.95};
+            auto cu_rate = [&](int g) { return base * (g == 1 ? kOne[mt] : kTwo[mt]) * 1e6; };   // flop per microsecond
             for (int s = 1; s <= (allow_split ? kMaxSplitsWs : 1); ++s) {
                 if (slices_all % (4 * s) != 0) continue;
+                if ((K / s) % 128 != 0 && tiles > 5 && mt != 5) continue;     // short fills exist in the five-tile form only
                 const double slices = (double)slices_all / s;
                 const double wg_flop = 2.0 * 32 * mt * cols * 16 * slices;
                 const long long blocks = (long long)tiles_m * (N / cols) * s;
                 auto round_time = [&](long long n) {                          // n work-groups dealt to the 256 CUs at once
                     const int g = (int)((n + 255) / 256);
-                    return std::max(g * wg_flop / cu_rate(g), slices * lone * (1.0 + 0.459 * (g - 1)));
+                    return std::max(g * wg_flop / cu_rate(g), slices * lone * (1.0 + 0.373 * (g - 1)));
                 };
                 const long long cap = 256LL * per_cu, full = blocks / cap, rem = blocks % cap;
                 double t = full * round_time(cap) + (rem ? round_time(rem) : 0.0);
-                t = std::max(t, 2.0 * M * (double)N * K / 1241.0e6);          // the chip's sustained rate
-                t = std::max(t, (double)N * K * 2.0 / 5.32e6);                // a weight stream cannot beat the memory system
-                if (s > 1) t += (double)s * M * N * 4.0 / 2.6e6;
+                t = std::max(t, 2.0 * M * (double)N * K / 1198.0e6);          // the chip's sustained rate
+                t = std::max(t, (double)N * K * 2.0 / 4.98e6);                // a weight stream cannot beat the memory system
+                if (s > 1) t += (double)s * M * N * 4.0 / 5.4e6 + (double)(s - 1) * M * N * 4.0 / 4.0e6;   // planes written here, read by the consumer
                 t += 2.3;
                 if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0, mt}; }
             }
@@ -945,6 +944,13 @@ extern "C" int sv_op_gemm_bf16_ws(const void* Ap, const void* Wp, float* out, in
         return SV_EINVAL;
     return gemm_bf16_ws((const bf16_t*)Ap, (const bf16_t*)Wp, out, M, N, K, splits, wide != 0, (hipStream_t)stream, row_tiles) == hipSuccess
                ? SV_OK : SV_EHIP;
+}
+
+extern "C" int sv_op_gemm_plan(int M, int N, int K, int* splits, int* wide, int* row_tiles) {
+    if (!splits || !wide || !row_tiles || M <= 0 || N <= 0 || K <= 0 || N % 128 != 0 || K % 64 != 0) return SV_EINVAL;
+    const WsPlan p = plan_ws(M, N, K, true);
+    *splits = p.splits; *wide = p.wide ? 1 : 0; *row_tiles = p.row_tiles;
+    return SV_OK;
 }
 
 extern "C" int sv_op_pack_rows(const void* src, void* dst, int M, int K, void* stream) {
