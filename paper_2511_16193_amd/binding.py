@@ -484,7 +484,7 @@ def op_sample_static(logits: torch.Tensor, drafts: torch.Tensor, draft_probs, un
     return acc, toks, best
 
 
-def probe_peaks(device="cuda:0", mfma_iters: int = 20000, copy_bytes: int = 1 << 30, copy_reps: int = 5) -> dict:
+def probe_peaks(device="cuda:0", mfma_iters: int = 60000, copy_bytes: int = 1 << 30, copy_reps: int = 5) -> dict:
     """The two micro-benchmarked rooflines of this GPU: dense bf16 MFMA rate on random operands (and on zeros),
     and the rate of a plain device copy."""
     dev = torch.device(device)
@@ -492,11 +492,14 @@ def probe_peaks(device="cuda:0", mfma_iters: int = 20000, copy_bytes: int = 1 <<
     sink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
     for name, ops in (("mfma_bf16_tflops_random_operands", torch.randn(256 * 256 * 64, device=dev).to(torch.bfloat16)),
                       ("mfma_bf16_tflops_zero_operands", torch.zeros(256 * 256 * 64, dtype=torch.bfloat16, device=dev))):
-        v = C.c_double()
-        rc = lib().sv_probe_mfma_bf16(_ptr(ops), ops.numel() * 2, _ptr(sink), mfma_iters, _stream_ptr(), C.byref(v))
-        if rc != 0:
-            raise SvError(rc, "sv_probe_mfma_bf16")
-        out[name] = v.value
+        best = 0.0
+        for _ in range(3):                      # the clock takes a few milliseconds of load to settle: best of three runs
+            v = C.c_double()
+            rc = lib().sv_probe_mfma_bf16(_ptr(ops), ops.numel() * 2, _ptr(sink), mfma_iters, _stream_ptr(), C.byref(v))
+            if rc != 0:
+                raise SvError(rc, "sv_probe_mfma_bf16")
+            best = max(best, v.value)
+        out[name] = best
     out["hbm_copy_gbs_read_plus_write"] = 2.0 * probe_copy(copy_bytes, copy_reps, dev)
     src = torch.ones(copy_bytes // 4, dtype=torch.float32, device=dev)
     flag = torch.zeros(1, dtype=torch.int32, device=dev)

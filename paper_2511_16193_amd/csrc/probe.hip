@@ -8,7 +8,7 @@
 #include "../../include/specverify_ops.h"
 #include "common.h"
 
-namespace {
+namespace sv {
 
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
@@ -70,7 +70,9 @@ struct EventPair {
     ~EventPair() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
 };
 
-}  // namespace
+}  // namespace sv
+
+using namespace sv;
 
 extern "C" int sv_probe_mfma_bf16(const void* operands, size_t operand_bytes, float* sink, int iters, void* stream,
                                   double* tflops) {
