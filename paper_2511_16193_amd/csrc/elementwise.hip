@@ -183,6 +183,59 @@ __global__ __launch_bounds__(64) void rope_append_kernel(RopeAppend p) {
     }
 }
 
+// The same with one work-group per row and four consecutive dimensions (and their partners half a head away) per
+// thread: 16-byte reads of the partial planes and of the rotary table, one 8- or 16-byte store per four q or K
+// values (four consecutive dimensions of a key are contiguous in the cache's K tiles); V is stored transposed, one
+// element at a time.  Needs head_dim % 8 == 0.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_vec_kernel(RopeAppend p) {
+    const int t = blockIdx.x, b = t / p.n;
+    const int hd = p.hd, half = hd / 2, upq = half / 4;   // units of four pairs per head
+    const int nheads = p.Hq + 2 * p.Hkv;
+    const int ncol = nheads * hd;
+    const int64_t stride = (int64_t)p.T * ncol;
+    const int slot = p.row_slot[t];
+    const int page = p.page_table[(int64_t)p.batch_seq[b] * p.max_pages_per_seq + slot / p.geom.page_size];
+    const int tok = slot % p.geom.page_size;
+    T* pool = reinterpret_cast<T*>(p.pool);
+    for (int u = threadIdx.x; u < nheads * upq; u += 256) {
+        const int head = u / upq, i = (u % upq) * 4;
+        const float* src = p.qkv_part + (int64_t)t * ncol + head * hd + i;
+        floatx4 x1 = {0.f, 0.f, 0.f, 0.f}, x2 = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < p.S; ++s) {
+            x1 += *reinterpret_cast<const floatx4*>(src + s * stride);
+            x2 += *reinterpret_cast<const floatx4*>(src + s * stride + half);
+        }
+        if (head < p.Hq + p.Hkv) {
+            const floatx4 r0 = *reinterpret_cast<const floatx4*>(p.rope + ((int64_t)t * half + i) * 2);
+            const floatx4 r1 = *reinterpret_cast<const floatx4*>(p.rope + ((int64_t)t * half + i) * 2 + 4);
+            const float c[4] = {r0[0], r0[2], r1[0], r1[2]}, sn[4] = {r0[1], r0[3], r1[1], r1[3]};
+            float o1[4], o2[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o1[e] = x1[e] * c[e] - x2[e] * sn[e];
+                o2[e] = x2[e] * c[e] + x1[e] * sn[e];
+            }
+            if (head < p.Hq) {
+                T* q = reinterpret_cast<T*>(p.q_out) + ((int64_t)t * p.Hq + head) * hd;
+                Store<T>::store4(q + i, o1);
+                Store<T>::store4(q + i + half, o2);
+            } else {
+                const int kh = head - p.Hq;
+                Store<T>::store4(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i), o1);
+                Store<T>::store4(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i + half), o2);
+            }
+        } else {
+            const int kh = head - p.Hq - p.Hkv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i + e), x1[e]);
+                Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i + half + e), x2[e]);
+            }
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ part, int S, int64_t stride,
                                                      T* __restrict__ act, int F, bool packed) {
@@ -271,6 +324,13 @@ hipError_t add_rmsnorm_experts(float* h, const float* y, const int32_t* inv, con
 }
 
 hipError_t rope_append(const RopeAppend& p, hipStream_t st) {
+    if (p.hd % 8 == 0) {
+        if (p.dtype == 1)
+            hipLaunchKernelGGL(rope_append_vec_kernel<bf16_t>, dim3(p.T), dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL(rope_append_vec_kernel<float>, dim3(p.T), dim3(256), 0, st, p);
+        return hipGetLastError();
+    }
     dim3 grid(p.T, p.Hq + 2 * p.Hkv);
     if (p.dtype == 1)
         hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, st, p);

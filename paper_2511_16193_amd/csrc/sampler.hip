@@ -34,17 +34,39 @@ __global__ __launch_bounds__(NT) void row_stats_kernel(const float* __restrict__
             s += expf((x - m) * inv_temp);
         }
     };
-    if ((V & 3) == 0) {                                   // rows start on 16-byte boundaries: four ids per load
-        for (int v = vbeg + 4 * threadIdx.x; v < vend; v += 4 * NT) {
-            const floatx4 x = *reinterpret_cast<const floatx4*>(row + v);
-            const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-            if (mx > m) {                                  // new maximum: its first holder among the four
-                s *= expf((m - mx) * inv_temp);            // (m = -inf: s is 0 and stays 0)
-                m = mx;
-                am = x[0] == mx ? v : x[1] == mx ? v + 1 : x[2] == mx ? v + 2 : v + 3;
+    if ((V & 3) == 0) {
+        // Rows start on 16-byte boundaries: four ids per load, and kAhead loads of a thread in flight before the
+        // arithmetic on any of them (one new maximum and one rescale per batch of loads, not per load).  The
+        // exponentials are the hardware's base-2 ones on pre-scaled arguments.
+        constexpr int kAhead = 5;
+        const float c2 = inv_temp * 1.4426950408889634f;
+        for (int v0 = vbeg + 4 * threadIdx.x; v0 < vend; v0 += 4 * NT * kAhead) {
+            floatx4 x[kAhead];
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int v = v0 + u * 4 * NT;
+                x[u] = v < vend ? *reinterpret_cast<const floatx4*>(row + v) : floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
             }
-            if (mx > -INFINITY)
-                s += (expf((x[0] - m) * inv_temp) + expf((x[1] - m) * inv_temp)) + (expf((x[2] - m) * inv_temp) + expf((x[3] - m) * inv_temp));
+            float mx = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) mx = fmaxf(mx, fmaxf(fmaxf(x[u][0], x[u][1]), fmaxf(x[u][2], x[u][3])));
+            if (mx > m) {                                  // new maximum: its first holder in ascending id order
+                s *= __builtin_amdgcn_exp2f((m - mx) * c2);   // (m = -inf: s is 0 and stays 0)
+                m = mx;
+#pragma unroll
+                for (int u = kAhead - 1; u >= 0; --u)
+#pragma unroll
+                    for (int i = 3; i >= 0; --i)
+                        if (x[u][i] == mx) am = v0 + u * 4 * NT + i;
+            }
+            if (mx > -INFINITY) {
+                float add = 0.f;
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u)
+                    add += (__builtin_amdgcn_exp2f((x[u][0] - m) * c2) + __builtin_amdgcn_exp2f((x[u][1] - m) * c2)) +
+                           (__builtin_amdgcn_exp2f((x[u][2] - m) * c2) + __builtin_amdgcn_exp2f((x[u][3] - m) * c2));
+                s += add;
+            }
         }
     } else {
         for (int v = vbeg + threadIdx.x; v < vend; v += NT) take(row[v], v);
