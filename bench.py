@@ -141,6 +141,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="skip the extra pass that replays the steps from a HIP graph")
     ap.add_argument("--attn-chunk", type=int, default=None, help="keys per split-KV chunk (tuning)")
     ap.add_argument("--attn-max-row-tiles", type=int, default=None, help="16-row tiles per attention work-group (tuning)")
+    ap.add_argument("--gemm-tile", type=int, default=None, choices=[-1, 0, 1],
+                    help="256 x 256 projection kernel: -1 where the plan expects it to pay (default), 0 never, 1 wherever the shape allows (tuning)")
     ap.add_argument("--drafts", choices=["noisy-target", "independent", "one-hot"], default="noisy-target",
                     help="independent: drafts from q = softmax(N(0,1)) without any device decoding step, so that "
                          "every kernel launch of the process has the timed step's shape (used for profiles); "
@@ -202,6 +204,8 @@ def main():
         case.ver.set_option(P.SV_OPT_ATTN_CHUNK_KEYS, args.attn_chunk)
     if args.attn_max_row_tiles is not None:
         case.ver.set_option(P.SV_OPT_ATTN_MAX_ROW_TILES, args.attn_max_row_tiles)
+    if args.gemm_tile is not None:
+        case.ver.set_option(P.SV_OPT_GEMM_TILE, args.gemm_tile)
     sigmas = None if args.sigma is None else [args.sigma]
     if args.drafts == "independent":
         log("drafting (target-independent q) ...")

@@ -29,13 +29,15 @@ int sv_op_gemm_bf16(const void *A, const void *W, float *out, int M, int N, int 
 /* The same projection with both operands in packed order, by the weight-streaming kernel: Ap = activations
  * packed by sv_op_pack_rows, Wp = weights packed by sv_op_pack_weight, out [splits, M, N] fp32.
  * wide != 0: 256 output features per work-group (N % 256 == 0), else 128.  K % (64*splits) == 0.
- * row_tiles: 32-row tiles per work-group, 1..5, or 0 = as few work-groups along the rows as five tiles each allow. */
+ * row_tiles: 32-row tiles per work-group, 1..5, or 0 = as few work-groups along the rows as five tiles each allow;
+ * 8 = the second packed-operand kernel instead (256 rows x 256 features per work-group, both operands through LDS:
+ * what the step uses from about a thousand rows on where its launch fills the chip; needs wide != 0). */
 int sv_op_gemm_bf16_ws(const void *Ap, const void *Wp, float *out, int M, int N, int K, int splits, int wide,
                        int row_tiles, void *stream);
 
 /* The launch shape verify_step gives the weight-streaming projection of M rows onto N features over K inputs
- * (HOST pointers out: reduction splits, 256- or 128-feature strips, 32-row tiles per work-group).  Host arithmetic
- * only.  N % 128 == 0, K % 64 == 0. */
+ * (HOST pointers out: reduction splits, 256- or 128-feature strips, 32-row tiles per work-group -- 8 = the 256 x 256
+ * kernel).  Host arithmetic only.  N % 128 == 0, K % 64 == 0. */
 int sv_op_gemm_plan(int M, int N, int K, int *splits, int *wide, int *row_tiles);
 
 /* Reorder row-major bf16 activations src [M, K] into dst (ceil(M/32)*32*K elements) in the order the
@@ -141,6 +143,8 @@ int sv_probe_hbm_read(const void *src, size_t bytes, int reps, void *sink, void 
 
 /* Tuning / diagnostic knobs of a context.
  *   SV_OPT_GEMM_VARIANT  work-group tile of the row-major bf16 projections (0..2; -1 = per shape, default)
+ *   SV_OPT_GEMM_TILE  the 256 x 256 kernel for packed projections: -1 = where the launch plan expects it to pay
+ *                     (default), 0 = never, 1 = wherever the shape allows (output features a multiple of 256)
  *   SV_OPT_ATTN_GENERIC  1 = always use the untuned one-wave-per-row attention (default 0)
  *   SV_OPT_ATTN_MIN_ROW_TILES  lower bound (1..4) on the 16-row tiles the bf16 attention is built for
  *   SV_OPT_ATTN_MAX_ROW_TILES  most 16-row tiles (1..4, default 4) one work-group of the bf16 attention takes;
@@ -151,7 +155,7 @@ int sv_probe_hbm_read(const void *src, size_t bytes, int reps, void *sink, void 
  *   SV_OPT_ATTN_CHUNK_KEYS  keys per split-KV chunk of the bf16 attention (multiple of 128, at least 1024; 0 = chosen per
  *                           batch from the lengths, default) */
 enum { SV_OPT_GEMM_VARIANT = 1, SV_OPT_ATTN_GENERIC = 2, SV_OPT_ATTN_MIN_ROW_TILES = 3, SV_OPT_ATTN_CHUNK_KEYS = 4,
-       SV_OPT_ATTN_MAX_ROW_TILES = 5, SV_OPT_GRAPH = 6 };
+       SV_OPT_ATTN_MAX_ROW_TILES = 5, SV_OPT_GRAPH = 6, SV_OPT_GEMM_TILE = 7 };
 int sv_set_option(sv_ctx *, int option, int value);
 
 #ifdef __cplusplus

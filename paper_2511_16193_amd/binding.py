@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libspecverify.so")
 SV_FP32, SV_BF16 = 0, 1
 SV_GREEDY, SV_STOCHASTIC, SV_MATCH = 0, 1, 2
 SV_INVERSE_CDF, SV_EXP_RACE = 0, 1
-SV_OPT_GEMM_VARIANT, SV_OPT_ATTN_GENERIC, SV_OPT_ATTN_MIN_ROW_TILES, SV_OPT_ATTN_CHUNK_KEYS, SV_OPT_ATTN_MAX_ROW_TILES, SV_OPT_GRAPH = 1, 2, 3, 4, 5, 6
+SV_OPT_GEMM_VARIANT, SV_OPT_ATTN_GENERIC, SV_OPT_ATTN_MIN_ROW_TILES, SV_OPT_ATTN_CHUNK_KEYS, SV_OPT_ATTN_MAX_ROW_TILES, SV_OPT_GRAPH, SV_OPT_GEMM_TILE = 1, 2, 3, 4, 5, 6, 7
 SV_PROF_GEMM, SV_PROF_ATTENTION, SV_PROF_SAMPLER, SV_PROF_ROLLBACK, SV_PROF_MOE = 0, 1, 2, 3, 4
 
 EXPORTS = [

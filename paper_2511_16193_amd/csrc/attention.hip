@@ -30,23 +30,6 @@ constexpr int TILE_KEYS = 32;
 
 struct KTile { u32x4 k[2][4]; u32x4 v[8]; };
 constexpr int kTileBytes = 2 * TILE_KEYS * HD * 2;     // K and V of one 32-key tile: 16 KB
-#define SV_ATTN_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-
-// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all-ones = no wait)
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
-__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
-
-// 4 KB from global memory straight into LDS: four wave-wide loads of 16 bytes per lane.  src is the lane's own
-// address (base + 16 * lane), dst the wave's LDS base; lane l's bytes land at dst + 16 * l + the immediate.
-__device__ __forceinline__ void dma4(const char* src, __attribute__((address_space(3))) void* dst) {
-    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 1024, 0);
-    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 2048, 0);
-    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 3072, 0);
-}
-
 // ---- Up to three row tiles in one work-group (at most 48 stacked rows) ----
 // Four waves per work-group, one work-group per CU (two with a single row tile); each wave has the next tile's
 // loads in flight in a second register set while it works on the current one.  Tile after tile per wave: scores,
@@ -438,8 +421,8 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
         const int64_t ke = uniform(head_base + (int64_t)page * a.geom.page_elems + off * HD + half * v_off);
         unsigned char* dst = ring + (half * D + slot) * 8192;
         const char* src = reinterpret_cast<const char*>(pool + ke) + lane_bytes;
-        dma4(src, SV_ATTN_LDS_PTR(dst));
-        dma4(src + 4096, SV_ATTN_LDS_PTR(dst + 4096));
+        dma4(src, SV_LDS_PTR(dst));
+        dma4(src + 4096, SV_LDS_PTR(dst + 4096));
     };
 
     // Wave w takes tiles w, w + 4, ... of the piece: its tile t starts at key tile_key(t).

@@ -89,6 +89,24 @@ __host__ __device__ __forceinline__ bool row_sees(int i, int j, int k) {
     return (i - 1) / k == (j - 1) / k && j <= i;
 }
 
+// ---- waits and direct-to-LDS loads ----
+#define SV_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all-ones = no wait)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// 4 KB from global memory straight into LDS: four wave-wide loads of 16 bytes per lane.  src is the lane's own
+// address (base + 16 * lane), dst the wave's LDS base; lane l's bytes land at dst + 16 * l + the immediate.
+__device__ __forceinline__ void dma4(const char* src, __attribute__((address_space(3))) void* dst) {
+    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 1024, 0);
+    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 2048, 0);
+    __builtin_amdgcn_global_load_lds((const void*)src, dst, 16, 3072, 0);
+}
+
 template <typename T> __device__ __forceinline__ T wave_max(T v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) { T w = __shfl_xor(v, o); v = w > v ? w : v; }

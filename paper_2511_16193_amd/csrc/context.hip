@@ -49,7 +49,7 @@ int pick_splits(int M, int N, int K) {
 // fit to a sweep of every (tiles, width, splits) over thirty shapes of the benchmark models on MI355X (rows 5 to
 // 2304); on that sweep the plan chosen is within 0.3 % of the best on average and 4.5 % at worst.
 struct WsPlan { int splits; bool wide; int row_tiles; };
-WsPlan plan_ws(int M, int N, int K, bool allow_split) {
+WsPlan plan_ws(int M, int N, int K, bool allow_split, int tile_mode = -1) {
     const int slices_all = K / 16;
     const int tiles = (M + 31) / 32;
     WsPlan best{1, false, gemm_bf16_ws_row_tiles(M)};
@@ -86,6 +86,12 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split) {
                 if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0, mt}; }
             }
         }
+    // The 256 x 256 kernel (row_tiles 8): rounds of 256 work-groups, each at the rate a CU sustains on such a tile.
+    if (tile_mode != 0 && N % 256 == 0 && K % 64 == 0) {
+        const long long blocks = (long long)((M + 255) / 256) * (N / 256);
+        const double t = (double)((blocks + 255) / 256) * 2.0 * 256 * 256 * K / (kTileRatePlain * 1e6) + 2.3;
+        if (tile_mode == 1 || (M >= 1024 && t < 0.97 * best_t)) best = WsPlan{1, true, 8};
+    }
     return best;
 }
 
@@ -204,6 +210,7 @@ struct sv_ctx {
     const int32_t* tok_len = nullptr;
     int tok_ld = 0, tok_col0 = 0;
     int gemm_variant;                                     // -1 = choose per shape
+    int gemm_tile;                                        // 256 x 256 projection kernel: -1 = where it pays, 0 = never, 1 = wherever the shape allows
     bool packed;                                          // projection weights are in fragment order
     bool attn_generic;
     int attn_min_rt;
@@ -344,6 +351,7 @@ extern "C" int verify_init(const sv_model* m, const sv_weights* w, const sv_runt
     for (int i = 0; i < r->num_pages; ++i) c->free_pages[i] = r->num_pages - 1 - i;   // pop_back yields 0,1,2..
     c->ring_pos = 0;
     c->gemm_variant = -1;
+    c->gemm_tile = -1;
     c->packed = w->packed != 0;
     c->attn_generic = false;
     c->attn_min_rt = 1;
@@ -589,7 +597,7 @@ static int gemm(sv_ctx* c, const void* A, const void* W, float* out, int M, int 
     if (c->model.dtype == SV_BF16) {
         if (c->packed) {
             // packed weights + packed activations: the weight-streaming kernel
-            const WsPlan p = plan_ws(M, N, K, allow_split);
+            const WsPlan p = plan_ws(M, N, K, allow_split, c->gemm_tile);
             *splits_out = p.splits;
             SV_HIP(c, gemm_bf16_ws((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, p.splits, p.wide, c->stream, p.row_tiles));
         } else {
@@ -725,7 +733,7 @@ static int layer_rows(sv_ctx* c, int l, int B, int n, int k, int max_len_ub, int
     if (c->packed && m.d_ff % 64 == 0) {
         // gate/up projection with SwiGLU in its epilogue: the [T, 2F] fp32 intermediate never exists
         ProfScope prof(c, SV_PROF_GEMM);
-        SV_HIP(c, gemm_bf16_ws_glu((const bf16_t*)a_norm, (const bf16_t*)c->wgu[l], c->at<bf16_t>(L.act), T, m.d_ff, d, st));
+        SV_HIP(c, gemm_bf16_ws_glu((const bf16_t*)a_norm, (const bf16_t*)c->wgu[l], c->at<bf16_t>(L.act), T, m.d_ff, d, st, c->gemm_tile));
     } else {
         int s_gu = 1;
         SV_TRY(gemm(c, a_norm, c->wgu[l], part, T, 2 * m.d_ff, d, &s_gu));
@@ -940,7 +948,7 @@ extern "C" int sv_op_gemm_bf16(const void* A, const void* W, float* out, int M, 
 extern "C" int sv_op_gemm_bf16_ws(const void* Ap, const void* Wp, float* out, int M, int N, int K, int splits, int wide,
                                   int row_tiles, void* stream) {
     if (!Ap || !Wp || !out || M <= 0 || N <= 0 || K <= 0 || splits <= 0 || N % (wide ? 256 : 128) != 0 ||
-        K % (64 * splits) != 0 || row_tiles < 0 || row_tiles > 5)
+        K % (64 * splits) != 0 || row_tiles < 0 || (row_tiles > 5 && row_tiles != 8) || (row_tiles == 8 && N % 256 != 0))
         return SV_EINVAL;
     return gemm_bf16_ws((const bf16_t*)Ap, (const bf16_t*)Wp, out, M, N, K, splits, wide != 0, (hipStream_t)stream, row_tiles) == hipSuccess
                ? SV_OK : SV_EHIP;
@@ -1168,6 +1176,10 @@ extern "C" int sv_set_option(sv_ctx* c, int option, int value) {
             if (value < -1 || value > 2)
                 return c->fail(SV_EINVAL, "gemm variant %d", value);
             c->gemm_variant = value;
+            return SV_OK;
+        case SV_OPT_GEMM_TILE:
+            if (value < -1 || value > 1) return c->fail(SV_EINVAL, "gemm tile mode %d", value);
+            c->gemm_tile = value;
             return SV_OK;
         case SV_OPT_ATTN_GENERIC:
             c->attn_generic = value != 0;

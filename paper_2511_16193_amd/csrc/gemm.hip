@@ -378,6 +378,237 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_ws_glu_mixed_kernel(
         gemm_bf16_ws_body<2, 1, 8, 8, true>(Ap, Wp, out, M, N, K, K, 1, tiles_m2, 2 * strips_tail, 2 * strips_main, blockIdx.x - n_main);
 }
 
+// ---- third bf16 kernel: 256 rows x 256 features per work-group, both operands through LDS ----
+// For a thousand rows and more the weights no longer dominate the traffic and what a work-group pulls through
+// the caches per product decides: a 256 x 256 tile asks for (256 + 256) x 32 bytes per 16-wide slice of the
+// reduction where the weight-streaming kernel's 160 x 256 asks for (160 + 256) x 32 for 5/8 of the products.
+// Four waves, each a 128 x 128 quarter (sixteen 32x32 accumulators); a fill is four slices of both operands,
+// 64 KB, copied global -> LDS by direct-to-LDS loads with no register in between (in the packed orders a fill
+// is sixteen contiguous 4 KB runs: four slices of one 32-row activation tile, or the four 32-feature tiles of
+// one 128-feature strip at one slice), double buffered, one barrier per fill.  Every wave reads its eight
+// operand fragments of a slice from LDS as 1 KB pieces, the next slice's between the products of this one.
+// Measured alone on MI355X (LM head, 2304 rows): 1.16 (K = 3584) and 1.21 PFLOP/s (K = 5120) against 1.02 and 1.06
+// of the weight-streaming kernel and 1.39 and 1.31 of the vendor library; the matrix unit is busy 62 % of the cycles.
+// GLU: the tile's features are 128 gate rows and the 128 up rows of the same features; a wave holds both for its
+// 64 features and writes silu(gate) * up, rounded to bf16, in the packed order of the next projection.
+template <bool GLU>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_tile_kernel(
+    const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Wp, float* __restrict__ out,
+    int M, int N, int K, int k_per_split, int splits, int tiles_m, int tiles_n) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char tile_lds[];   // two fills
+    constexpr int KA = 4;                                 // 16-wide slices per fill
+    constexpr int FILL = KA * 16 * 1024;                  // KA slices of 8 activation and 8 weight fragments
+    constexpr int B_OFF = KA * 8 * 1024;                  // weights behind the activations of a fill
+    constexpr int RW = KA / 2;                            // 4 KB weight runs (strip, slice) per wave and fill
+    constexpr int LPF = 4 * KA;                           // loads per wave and fill
+
+    const int nblk = tiles_m * tiles_n * splits;
+    int logical = xcd_remap(blockIdx.x, nblk);
+    const int tm = logical % tiles_m;
+    logical /= tiles_m;
+    const int sp = logical % splits;
+    const int tn = logical / splits;
+    const int m0 = tm * 256;
+    const int ks0 = sp * (k_per_split / 16);
+    const int nfill = k_per_split / (16 * KA);
+    const int kslices = K / 16;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lg = lane >> 5;
+    const int m_tiles_total = (M + 31) / 32;
+
+    // this wave's share of a fill: activation row tiles 2 wave, 2 wave + 1 (KA slices each, contiguous) and RW of
+    // the 2 KA weight runs (strip, slice), 4 KB each
+    const char* a_src[2];
+    const char* w_src[RW];
+    int a_dst[2], w_dst[RW];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        int mt = m0 / 32 + 2 * wave + i;
+        mt = mt < m_tiles_total ? mt : m_tiles_total - 1;        // rows beyond M: any valid tile, never stored
+        a_src[i] = reinterpret_cast<const char*>(Ap + ((int64_t)mt * kslices + ks0) * 512) + lane * 16;
+        a_dst[i] = (2 * wave + i) * KA * 1024;
+    }
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+        const int run = wave * RW + i, strip = run / KA, sl = run % KA;
+        const int strip_g = GLU ? (strip == 0 ? tn : N / 256 + tn) : 2 * tn + strip;
+        w_src[i] = reinterpret_cast<const char*>(Wp + (((int64_t)strip_g * kslices + ks0 + sl) * 4) * 512) + lane * 16;
+        w_dst[i] = B_OFF + (strip * KA + sl) * 4096;
+    }
+    auto issue_fill = [&](int fill, int buf) __attribute__((always_inline)) {
+        unsigned char* base = tile_lds + buf * FILL;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const char* src = a_src[i] + (int64_t)fill * (KA * 1024);
+            dma4(src, SV_LDS_PTR(base + a_dst[i]));
+        }
+#pragma unroll
+        for (int i = 0; i < RW; ++i) dma4(w_src[i] + (int64_t)fill * (KA * 4096), SV_LDS_PTR(base + w_dst[i]));
+    };
+    // fragment offsets of this wave inside a fill, slice 0
+    int a_off[4], b_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a_off[j] = ((wm * 4 + j) * KA) * 1024 + lane * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int strip = GLU ? (i >> 1) : wn, tile = GLU ? 2 * wn + (i & 1) : i;
+        b_off[i] = B_OFF + (strip * KA * 4 + tile) * 1024 + lane * 16;
+    }
+
+    floatx16 acc[4][4];                                   // [feature tile i][row tile j]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // The loop is written out instruction by instruction.  A wave alone on its SIMD issues in order, and the matrix
+    // unit runs dry whenever anything else is issued in a block: with the eight LDS reads of a slice and the sixteen
+    // loads of a fill issued together it was busy 55 % of the cycles.  So one LDS read (of the next slice) or one
+    // group of loads (of the fill after next) follows each product and executes in its shadow.  The reads are
+    // hand-placed instructions with hand-counted waits because a direct-to-LDS load in flight makes the compiler
+    // wait for every LDS read at once.
+    u32x4 af[2][4], wf[2][4];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)SV_LDS_PTR(tile_lds);
+    uint32_t a_addr[4], b_addr[4];
+    auto set_buf = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a_addr[j] = lds0 + buf * FILL + a_off[j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b_addr[i] = lds0 + buf * FILL + b_off[i];
+    };
+#define SV_FENCE __builtin_amdgcn_sched_barrier(0)
+#define SV_RA(SET, J, S) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(af[SET][J]) : "v"(a_addr[J]), "n"((S) * 1024))
+#define SV_RB(SET, I, S) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wf[SET][I]) : "v"(b_addr[I]), "n"((S) * 4096))
+    // gated form: weights first, so that a lane holds one row and consecutive features; plain form: activations first,
+    // so that a lane holds one feature and a half wave writes 128 contiguous bytes
+#define SV_MF(SET, I, J)                                                                                              \
+    acc[I][J] = GLU ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[SET][I]),                 \
+                                                              __builtin_bit_cast(bf16x8, af[SET][J]), acc[I][J], 0, 0, 0) \
+                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[SET][J]),                 \
+                                                              __builtin_bit_cast(bf16x8, wf[SET][I]), acc[I][J], 0, 0, 0)
+    // the products of one slice (operands in SET), the reads of slice S into the other set woven into the first half
+#define SV_SLICE_HEAD(SET, S)                                                                                         \
+    SV_FENCE; SV_MF(SET, 0, 0); SV_MF(SET, 0, 1); SV_FENCE; SV_RA(1 - SET, 0, S); SV_RA(1 - SET, 1, S); SV_FENCE;     \
+    SV_MF(SET, 0, 2); SV_MF(SET, 0, 3); SV_FENCE; SV_RA(1 - SET, 2, S); SV_RA(1 - SET, 3, S); SV_FENCE;               \
+    SV_MF(SET, 1, 0); SV_MF(SET, 1, 1); SV_FENCE; SV_RB(1 - SET, 0, S); SV_FENCE;                                     \
+    SV_MF(SET, 1, 2); SV_MF(SET, 1, 3); SV_FENCE; SV_RB(1 - SET, 1, S); SV_FENCE
+#define SV_SLICE_TAIL(SET, S)                                                                                         \
+    SV_MF(SET, 2, 0); SV_MF(SET, 2, 1); SV_FENCE; SV_RB(1 - SET, 2, S); SV_FENCE;                                     \
+    SV_MF(SET, 2, 2); SV_MF(SET, 2, 3); SV_FENCE; SV_RB(1 - SET, 3, S); SV_FENCE;                                     \
+    SV_MF(SET, 3, 0); SV_MF(SET, 3, 1); SV_MF(SET, 3, 2); SV_MF(SET, 3, 3); SV_FENCE
+
+    issue_fill(0, 0);
+    issue_fill(nfill > 1 ? 1 : 0, 1);
+    wait_vmcnt<LPF>();                                    // the first fill has landed (loads return in order)
+    __builtin_amdgcn_s_barrier();
+    set_buf(0);
+    SV_RA(0, 0, 0); SV_RA(0, 1, 0); SV_RA(0, 2, 0); SV_RA(0, 3, 0);
+    SV_RB(0, 0, 0); SV_RB(0, 1, 0); SV_RB(0, 2, 0); SV_RB(0, 3, 0);
+    for (int fill = 0; fill < nfill; ++fill) {
+        const int buf = fill & 1;
+        wait_lgkmcnt0();
+        SV_SLICE_HEAD(0, 1); SV_SLICE_TAIL(0, 1);
+        wait_lgkmcnt0();
+        SV_SLICE_HEAD(1, 2); SV_SLICE_TAIL(1, 2);
+        wait_lgkmcnt0();
+        SV_SLICE_HEAD(0, 3); SV_SLICE_TAIL(0, 3);
+        // This wave holds everything it needs of the buffer; its share of the next fill has landed; after the barrier
+        // so has everyone's, and nobody reads this buffer any more.
+        wait_lgkmcnt0();
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        set_buf(buf ^ 1);
+        // last slice: the first slice of the next fill is read, and the fill after next (past the end: the last one
+        // again, so that the loop has no branch) is requested into the buffer just given up
+        SV_SLICE_HEAD(1, 0);
+        {
+            const int ahead = fill + 2 < nfill ? fill + 2 : nfill - 1;
+            unsigned char* base = tile_lds + buf * FILL;
+            SV_MF(1, 2, 0); SV_MF(1, 2, 1); SV_FENCE; SV_RB(0, 2, 0); SV_FENCE;
+            dma4(a_src[0] + (int64_t)ahead * (KA * 1024), SV_LDS_PTR(base + a_dst[0])); SV_FENCE;
+            SV_MF(1, 2, 2); SV_MF(1, 2, 3); SV_FENCE; SV_RB(0, 3, 0); SV_FENCE;
+            dma4(a_src[1] + (int64_t)ahead * (KA * 1024), SV_LDS_PTR(base + a_dst[1])); SV_FENCE;
+            SV_MF(1, 3, 0); SV_MF(1, 3, 1); SV_FENCE;
+            dma4(w_src[0] + (int64_t)ahead * (KA * 4096), SV_LDS_PTR(base + w_dst[0])); SV_FENCE;
+            SV_MF(1, 3, 2); SV_MF(1, 3, 3); SV_FENCE;
+            dma4(w_src[1] + (int64_t)ahead * (KA * 4096), SV_LDS_PTR(base + w_dst[1])); SV_FENCE;
+        }
+    }
+    wait_lgkmcnt0();
+#undef SV_FENCE
+#undef SV_RA
+#undef SV_RB
+#undef SV_MF
+#undef SV_SLICE_HEAD
+#undef SV_SLICE_TAIL
+    wait_vmcnt<0>();                                      // nothing of this work-group may land in LDS after it has gone
+
+    if (GLU) {
+        const int F = N / 2;
+        bf16_t* act = reinterpret_cast<bf16_t*>(out);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int fs = (tn * 128 + (2 * wn + i) * 32) / 16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int mt = m0 / 32 + wm * 4 + j;
+                if (mt < m_tiles_total) {
+                    bf16_t* dst = act + ((int64_t)mt * (F / 16) + fs) * 512;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float r[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float g = acc[i][j][4 * q + e];
+                            r[e] = g / (1.0f + expf(-g)) * acc[2 + i][j][4 * q + e];
+                        }
+                        u32x2 pk = {pack2bf(r[0], r[1]), pack2bf(r[2], r[3])};
+                        *reinterpret_cast<u32x2*>(dst + ((q >> 1) * 64 + l32 + 32 * (q & 1)) * 8 + 4 * lg) = pk;
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // acc[i][j][4 q + r] <-> row m0 + 32 (4 wm + j) + 8 q + 4 lg + r, feature 256 tn + 32 (4 wn + i) + l32
+    float* dst = out + (int64_t)sp * M * N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = tn * 256 + (wn * 4 + i) * 32 + l32;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (wm * 4 + j) * 32 + 8 * q + 4 * lg + r;
+                    if (m < M) dst[(int64_t)m * N + n] = acc[i][j][4 * q + r];
+                }
+    }
+}
+
+// plain: out [splits][M][N] fp32, N % 256 == 0.  gated: N = 2 F weight rows, out = packed bf16 [ceil(M/32)*32, F],
+// F % 128 == 0, splits == 1.  (K / splits) % 64 == 0.
+hipError_t gemm_bf16_tile(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool glu, hipStream_t st) {
+    if (splits < 1 || K % splits != 0 || (K / splits) % 64 != 0 || N % 256 != 0 || (glu && splits != 1))
+        return hipErrorInvalidValue;
+    const int tiles_m = (M + 255) / 256, tiles_n = glu ? N / 2 / 128 : N / 256;
+    auto launch = [&](auto kern) -> hipError_t {
+        const size_t lds = 2 * 4 * 16 * 1024;             // two fills of four slices
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(256), lds, st, Ap, Wp, out, M, N, K, K / splits, splits,
+                           tiles_m, tiles_n);
+        return hipGetLastError();
+    };
+    return glu ? launch(gemm_bf16_tile_kernel<true>) : launch(gemm_bf16_tile_kernel<false>);
+}
+
 // Activations [M, K] row-major -> packed [ceil(M/32)][K/16][64 lanes][8]: lane 32*g + r of a fragment holds
 // row 32*tile + r, elements 8*g .. 8*g+7 of the slice; rows beyond M are written as zeros.
 __global__ void pack_rows_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int M, int K) {
@@ -411,9 +642,16 @@ static hipError_t launch_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int 
 
 // Gate/up projection fused with SwiGLU: Wp packed [2F, K] (gate rows, then up rows); act_out packed
 // [ceil(M/32)*32, F] bf16.  F a multiple of 64.
-hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st) {
+hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st, int tile_mode) {
     if (F % 64 != 0 || K % 64 != 0) return hipErrorInvalidValue;
     float* out = reinterpret_cast<float*>(act_out);
+    if (F % 128 == 0 && tile_mode != 0) {
+        // From a thousand rows on the 256-row tiles win where their launch fills its rounds about as well as the
+        // 160-row one does: rounds x rows per work-group / the rate a CU reaches with either (TFLOP/s, measured).
+        const long long n_ws = (long long)((M + 159) / 160) * (F / 128), n_tile = (long long)((M + 255) / 256) * (F / 128);
+        const double t_ws = (double)((n_ws + 255) / 256) * 160.0 / 4.47, t_tile = (double)((n_tile + 255) / 256) * 256.0 / kTileRateGlu;
+        if (tile_mode == 1 || (M >= 1024 && t_tile < 0.97 * t_ws)) return gemm_bf16_tile(Ap, Wp, out, M, 2 * F, K, 1, true, st);
+    }
     if (F % 128 == 0 && K % 128 == 0) {
         // 128-feature strips, gate and up in one wave.  One work-group per CU: the launch runs in rounds of 256,
         // and a last round that is less than half full would leave most CUs idle for a whole work-group's time.
@@ -466,6 +704,7 @@ int gemm_bf16_ws_row_tiles(int M) {
 
 hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool wide,
                         hipStream_t st, int row_tiles) {
+    if (row_tiles == 8) return gemm_bf16_tile(Ap, Wp, out, M, N, K, splits, false, st);
     const bool long_fill = (K / splits) % 128 == 0;
     if (!long_fill)          // short reductions (small models): the five-tile form only
         return wide ? launch_ws<5, 2, 4, 4>(Ap, Wp, out, M, N, K, splits, st) : launch_ws<5, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);

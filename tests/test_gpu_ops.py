@@ -54,6 +54,21 @@ def test_gemm_weight_streaming_matches_float64_product(M_, N, K, splits, wide):
         assert np.max(np.abs(got - want)) < 1e-4, row_tiles
 
 
+@pytest.mark.parametrize("M_,N,K,splits", [(256, 256, 64, 1), (700, 512, 448, 1), (1, 256, 2048, 2), (1290, 768, 3584, 1),
+                                           (513, 1024, 1536, 4)])
+def test_gemm_256_tile_kernel_matches_float64_product(M_, N, K, splits):
+    """The 256 x 256 kernel (both operands through LDS; row_tiles = 8 selects it): whole and ragged row blocks (rows
+    beyond M read as the last tile and are never stored), one to many fills of four k-slices, split reductions."""
+    from paper_2511_16193_amd import op_gemm_bf16_ws, op_pack_weight, op_pack_rows
+    a = bf16_cpu((M_, K), 1.0, 1)
+    w = bf16_cpu((N, K), 0.02, 2)
+    want = M.matmul_wt(a.float().numpy().astype(np.float64), w.float().numpy())
+    got = op_gemm_bf16_ws(op_pack_rows(a.to(DEV)), op_pack_weight(w.to(DEV)), M_, splits=splits, wide=True, row_tiles=8)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64).sum(axis=0)
+    assert np.max(np.abs(got - want)) < 1e-4
+
+
 @pytest.mark.parametrize("k,n_chains,group", [(0, 1, 7), (1, 1, 7), (2, 1, 7), (4, 1, 7), (8, 1, 7), (4, 1, 8), (3, 3, 4),
                                               (8, 3, 5)])
 def test_attention_bf16_matches_oracle(k, n_chains, group):

@@ -196,6 +196,33 @@ def test_bf16_wide_ffn_gate_up_launch_with_a_short_last_round():
     case.close()
 
 
+TALL_BATCH = W.Shape("tall-batch-bf16", 2, 256, 8, 2, 128, 1152, 2048, dtype="bf16", batch=258, k=4, seed=93)
+
+
+def test_bf16_step_through_the_256_row_projection_kernel():
+    """1290 rows (258 requests, k = 4) with the 256 x 256 projection kernel forced on for every projection whose
+    output is a multiple of 256 wide (QKV, O, the LM head, and the gated gate/up form with its bf16 epilogue): five
+    whole row blocks and one of ten rows, nine gate/up strips, reductions of four and of eighteen fills.  Logits and
+    decisions against the oracle; lengths after the rollback."""
+    import paper_2511_16193_amd as P
+    shape = TALL_BATCH
+    B, V, k = shape.batch, shape.vocab, shape.k
+    lengths = [3 + (11 * b) % 70 for b in range(B)]
+    case = Case(shape, lengths, verify_mode=OV.STOCHASTIC, sample_mode=OV.SAMPLE_EXP_RACE, packed=True)
+    case.ver.set_option(P.SV_OPT_GEMM_TILE, 1)
+    x0 = W.make_tokens((B,), V, shape.seed, "x0")
+    q = W.make_random_q((B, 1, k), V, 1.0, shape.seed)
+    drafts = W.sample_from(q, shape.seed).numpy()
+    u = W.make_uniforms((B, 1, k + 1), shape.seed)
+    r, g = case.step(x0, drafts, q, u)
+    err, exempt, diverged = compare_step(r, g, "bf16", k)
+    assert err < LOGIT_TOL["bf16"]
+    assert len(diverged) <= max(1, B // 8)
+    keep = np.array([b not in diverged for b in range(B)])
+    assert np.array_equal(case.device_lengths()[keep], np.array([c.length for c in case.caches])[keep])
+    case.close()
+
+
 @pytest.mark.parametrize("packed", [False, True])
 def test_bf16_prefill_then_step(packed):
     """Real prefill on both sides (no synthetic cache): prompts of 150 tokens run through verify_prefill in chunks,
