@@ -86,11 +86,12 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split, int tile_mode = -1) {
                 if (t < best_t - 1e-9) { best_t = t; best = WsPlan{s, wide != 0, mt}; }
             }
         }
-    // The 256 x 256 kernel (row_tiles 8): rounds of 256 work-groups, each at the rate a CU sustains on such a tile.
+    // The 256 x 256 kernel (row_tiles 8) from a thousand rows on, where its tiles fill the chip at least four times
+    // over (the LM head): measured inside the steps of the 7B shape it takes 8 % off that launch at 1280 and at 2304
+    // rows.  Narrower projections (QKV, O, down: fewer tiles than CUs) stay with the weight-streaming kernel.
     if (tile_mode != 0 && N % 256 == 0 && K % 64 == 0) {
         const long long blocks = (long long)((M + 255) / 256) * (N / 256);
-        const double t = (double)((blocks + 255) / 256) * 2.0 * 256 * 256 * K / (kTileRatePlain * 1e6) + 2.3;
-        if (tile_mode == 1 || (M >= 1024 && t < 0.97 * best_t)) best = WsPlan{1, true, 8};
+        if (tile_mode == 1 || (M >= 1024 && blocks >= 4 * 256)) best = WsPlan{1, true, 8};
     }
     return best;
 }

@@ -20,8 +20,8 @@ int gemm_bf16_ws_row_tiles(int M);
 // 256 x 256 tiles, both operands through LDS (for a thousand rows and more).  glu: N = 2 F gate and up rows, out =
 // packed bf16 activations [ceil(M/32)*32, F]
 hipError_t gemm_bf16_tile(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, int N, int K, int splits, bool glu, hipStream_t st);
-// what a CU sustains on 256 x 256 tiles, TFLOP/s: fp32 output, gated bf16 output (measured on MI355X)
-constexpr double kTileRatePlain = 4.35, kTileRateGlu = 4.6;
+// what a CU sustains on 256 x 256 tiles with the gated bf16 output, TFLOP/s (measured inside a step on MI355X)
+constexpr double kTileRateGlu = 4.85;
 // tile_mode: -1 = the 256 x 256 kernel where it pays, 0 = never, 1 = whenever the shape allows
 hipError_t gemm_bf16_ws_glu(const bf16_t* Ap, const bf16_t* Wp, bf16_t* act_out, int M, int F, int K, hipStream_t st, int tile_mode = -1);
 hipError_t gemm_f32(const float* A, const float* W, float* out, int M, int N, int K, hipStream_t st);
