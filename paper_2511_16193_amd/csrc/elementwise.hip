@@ -145,48 +145,10 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
     }
 }
 
-// One wave per (row, head): q and k heads are rotated, k and v heads go to the row's cache slot.
-template <typename T>
-__global__ __launch_bounds__(64) void rope_append_kernel(RopeAppend p) {
-    const int t = blockIdx.x, head = blockIdx.y, b = t / p.n;
-    const int hd = p.hd, half = hd / 2;
-    const int ncol = (p.Hq + 2 * p.Hkv) * hd;
-    const int64_t stride = (int64_t)p.T * ncol;
-    const float* src = p.qkv_part + (int64_t)t * ncol + head * hd;
-    const int slot = p.row_slot[t];
-    const int page = p.page_table[(int64_t)p.batch_seq[b] * p.max_pages_per_seq + slot / p.geom.page_size];
-    const int tok = slot % p.geom.page_size;
-    T* pool = reinterpret_cast<T*>(p.pool);
-    for (int i = threadIdx.x; i < half; i += 64) {
-        float x1 = 0.f, x2 = 0.f;
-        for (int s = 0; s < p.S; ++s) {
-            x1 += src[s * stride + i];
-            x2 += src[s * stride + i + half];
-        }
-        if (head < p.Hq + p.Hkv) {
-            const float c = p.rope[((int64_t)t * half + i) * 2], sn = p.rope[((int64_t)t * half + i) * 2 + 1];
-            const float o1 = x1 * c - x2 * sn, o2 = x2 * c + x1 * sn;
-            if (head < p.Hq) {
-                T* q = reinterpret_cast<T*>(p.q_out) + ((int64_t)t * p.Hq + head) * hd;
-                Store<T>::store(q + i, o1);
-                Store<T>::store(q + i + half, o2);
-            } else {
-                const int kh = head - p.Hq;
-                Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i), o1);
-                Store<T>::store(pool + kv_k_index(p.geom, p.layer, page, kh, tok, i + half), o2);
-            }
-        } else {
-            const int kh = head - p.Hq - p.Hkv;
-            Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i), x1);
-            Store<T>::store(pool + kv_v_index(p.geom, p.layer, page, kh, tok, i + half), x2);
-        }
-    }
-}
-
-// The same with one work-group per row and four consecutive dimensions (and their partners half a head away) per
-// thread: 16-byte reads of the partial planes and of the rotary table, one 8- or 16-byte store per four q or K
-// values (four consecutive dimensions of a key are contiguous in the cache's K tiles); V is stored transposed, one
-// element at a time.  Needs head_dim % 8 == 0.
+// q and k heads are rotated, k and v heads go to the row's cache slot.  One work-group per row, four consecutive
+// dimensions (and their partners half a head away) per thread: 16-byte reads of the partial planes and of the
+// rotary table, one 8- or 16-byte store per four q or K values (four consecutive dimensions of a key are contiguous
+// in the cache's K tiles); V is stored transposed, one element at a time.  head_dim % 8 == 0 (it is 64 or 128).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_append_vec_kernel(RopeAppend p) {
     const int t = blockIdx.x, b = t / p.n;
@@ -324,18 +286,11 @@ hipError_t add_rmsnorm_experts(float* h, const float* y, const int32_t* inv, con
 }
 
 hipError_t rope_append(const RopeAppend& p, hipStream_t st) {
-    if (p.hd % 8 == 0) {
-        if (p.dtype == 1)
-            hipLaunchKernelGGL(rope_append_vec_kernel<bf16_t>, dim3(p.T), dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL(rope_append_vec_kernel<float>, dim3(p.T), dim3(256), 0, st, p);
-        return hipGetLastError();
-    }
-    dim3 grid(p.T, p.Hq + 2 * p.Hkv);
+    if (p.hd % 8 != 0) return hipErrorInvalidValue;
     if (p.dtype == 1)
-        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL(rope_append_vec_kernel<bf16_t>, dim3(p.T), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(rope_append_kernel<float>, grid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL(rope_append_vec_kernel<float>, dim3(p.T), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
