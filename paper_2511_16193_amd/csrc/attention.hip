@@ -30,6 +30,19 @@ constexpr int TILE_KEYS = 32;
 
 struct KTile { u32x4 k[2][4]; u32x4 v[8]; };
 constexpr int kTileBytes = 2 * TILE_KEYS * HD * 2;     // K and V of one 32-key tile: 16 KB
+// Largest of the eight scores a lane holds of one row tile, for the kernel whose time is its instruction count (the
+// skewed one below).  Written as the instructions themselves: through fmaxf the compiler first passes every score
+// through a v_max_f32 x, x, x of its own (it must assume signalling NaNs in what an MFMA returns), eleven
+// instructions where four do.
+__device__ __forceinline__ float max8(const floatx4& a, const floatx4& b) {
+    float r, t;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a[0]), "v"(a[1]), "v"(a[2]));
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(t) : "v"(a[3]), "v"(b[0]), "v"(b[1]));
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(r), "v"(b[2]), "v"(b[3]));
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(r), "v"(t));
+    return r;
+}
+
 // ---- Up to three row tiles in one work-group (at most 48 stacked rows) ----
 // Four waves per work-group, one work-group per CU (two with a single row tile); each wave has the next tile's
 // loads in flight in a second register set while it works on the current one.  Tile after tile per wave: scores,
@@ -523,8 +536,7 @@ __global__ __launch_bounds__(64 * W, 1) void attn_bf16_kernel(AttnArgs a, float 
             float lmax[R];
 #pragma unroll
             for (int rt = 0; rt < R; ++rt) {
-                lmax[rt] = fmaxf(fmaxf(fmaxf(s_cur[0][rt][0], s_cur[0][rt][1]), fmaxf(s_cur[0][rt][2], s_cur[0][rt][3])),
-                                 fmaxf(fmaxf(s_cur[1][rt][0], s_cur[1][rt][1]), fmaxf(s_cur[1][rt][2], s_cur[1][rt][3])));
+                lmax[rt] = max8(s_cur[0][rt], s_cur[1][rt]);
                 trig |= ((m_run[rt] == -INFINITY) & (lmax[rt] > -INFINITY)) | (fmaf(lmax[rt], scale_log2e, -mc[rt]) > 16.0f);
             }
             if (QK) {
