@@ -47,7 +47,8 @@ int pick_splits(int M, int N, int K) {
 // sustains about 1.2 PFLOP/s on random data (it is power-limited well below the MFMA peak) and 5 TB/s of
 // weights; a partial plane costs its bytes, written here and read again by the consumer.  The constants are a
 // fit to a sweep of every (tiles, width, splits) over thirty shapes of the benchmark models on MI355X (rows 5 to
-// 2304); on that sweep the plan chosen is within 0.3 % of the best on average and 4.5 % at worst.
+// 2304), except the lone work-group's pace, which is taken from whole steps (cold weights); on the sweep the plan
+// chosen was within 0.3 % of the best on average and 4.5 % at worst.
 struct WsPlan { int splits; bool wide; int row_tiles; };
 WsPlan plan_ws(int M, int N, int K, bool allow_split, int tile_mode = -1) {
     const int slices_all = K / 16;
@@ -63,7 +64,9 @@ WsPlan plan_ws(int M, int N, int K, bool allow_split, int tile_mode = -1) {
             const int tiles_m = (tiles + mt - 1) / mt;
             const int per_cu = (wide && mt >= 4) ? 1 : 2;                     // work-groups resident per CU
             const double base = wide ? 5.19 : 4.14;                           // TFLOP/s of a CU at full tile height
-            const double lone = wide ? 0.0883 : 0.0683;                       // us per slice a lone work-group cannot beat
+            // us per slice a lone work-group cannot beat: inside a step a layer's weights come cold from HBM (32 KB in
+            // flight per work-group against ~1 us of latency), twice what a sweep of one projection in a loop shows
+            const double lone = wide ? 0.17 : 0.13;
             // share of that rate a CU reaches with one resp. two work-groups of mt tiles
             static const double kOne[6] = {0, 0.56, 0.97, 0.94, 0.93, 0.98}, kTwo[6] = {0, 0.58, 0.82, 0.90, 0.96, 0.95};
             auto cu_rate = [&](int g) { return base * (g == 1 ? kOne[mt] : kTwo[mt]) * 1e6; };   // flop per microsecond

@@ -706,9 +706,13 @@ hipError_t gemm_bf16_ws(const bf16_t* Ap, const bf16_t* Wp, float* out, int M, i
                         hipStream_t st, int row_tiles) {
     if (row_tiles == 8) return gemm_bf16_tile(Ap, Wp, out, M, N, K, splits, false, st);
     const bool long_fill = (K / splits) % 128 == 0;
-    if (!long_fill)          // short reductions (small models): the five-tile form only
-        return wide ? launch_ws<5, 2, 4, 4>(Ap, Wp, out, M, N, K, splits, st) : launch_ws<5, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
     const int mt = row_tiles >= 1 && row_tiles <= 5 ? row_tiles : gemm_bf16_ws_row_tiles(M);
+    if (!long_fill) {        // short fills (small models; many splits of a deep reduction at a few rows): narrow strips of
+                             // one or two row tiles, else the five-tile form
+        if (!wide && mt == 1) return launch_ws<1, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
+        if (!wide && mt == 2) return launch_ws<2, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
+        return wide ? launch_ws<5, 2, 4, 4>(Ap, Wp, out, M, N, K, splits, st) : launch_ws<5, 1, 4, 4>(Ap, Wp, out, M, N, K, splits, st);
+    }
     switch (mt * 2 + (wide ? 1 : 0)) {
         case 2: return launch_ws<1, 1, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
         case 3: return launch_ws<1, 2, 8, 8>(Ap, Wp, out, M, N, K, splits, st);
