@@ -49,3 +49,26 @@ def test_invalid_descriptions_are_rejected_without_a_gpu():
     assert lib.verify_workspace_bytes(ctypes.byref(m), ctypes.byref(rt)) == 0
     ctx = ctypes.c_void_p()
     assert lib.verify_init(ctypes.byref(m), None, ctypes.byref(rt), None, ctypes.byref(ctx)) == -1
+
+
+def test_launch_plans_are_launchable_shapes():
+    """sv_op_gemm_plan is host arithmetic: every plan it hands out for the benchmark models' projections must be a
+    shape the packed-operand kernels accept -- the reduction cut into whole fills, 256-feature strips only where the
+    width allows, one to five 32-row tiles per work-group or the 256 x 256 kernel (8), and that one only from a
+    thousand rows on."""
+    from paper_2511_16193_amd import op_gemm_plan
+    shapes = [(4608, 3584), (3584, 3584), (37888, 3584), (3584, 18944), (152064, 3584),      # 7B: QKV, O, gate/up, down, LM head
+              (7168, 5120), (5120, 5120), (55296, 5120), (5120, 27648), (152064, 5120),      # 32B
+              (5120, 2048), (2048, 4096), (151936, 2048), (2048, 256), (256, 1024)]          # MoE model, tiny models
+    for M in (1, 5, 40, 160, 320, 640, 800, 1000, 1280, 2048, 2304):
+        for N, K in shapes:
+            p = op_gemm_plan(M, N, K)
+            s, mt = p["splits"], p["row_tiles"]
+            assert 1 <= s <= 16 and K % (64 * s) == 0, (M, N, K, p)
+            assert not p["wide"] or N % 256 == 0, (M, N, K, p)
+            assert mt in (1, 2, 3, 4, 5, 8), (M, N, K, p)
+            if mt == 8:
+                assert M >= 1024 and p["wide"] and s == 1 and K % 64 == 0, (M, N, K, p)
+                assert ((M + 255) // 256) * (N // 256) >= 1024, (M, N, K, p)
+            else:
+                assert mt * 32 * ((M + 32 * mt - 1) // (32 * mt)) < M + 32 * mt, (M, N, K, p)   # no work-group made of padding alone
