@@ -177,7 +177,9 @@ def main():
     # a stream of its own for everything: the library can only capture its launches into a graph off the null stream
     torch.cuda.set_stream(torch.cuda.Stream())
     if args.calibrate_peaks:
-        print(json.dumps(P.probe_peaks()), flush=True)
+        peaks = P.probe_peaks()
+        peaks["mfma_and_valu_overlap"] = P.probe_mfma_valu()
+        print(json.dumps(peaks), flush=True)
         return
     shape = W.CONFIGS[args.config]
     if args.batch is not None:

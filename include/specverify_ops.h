@@ -140,6 +140,11 @@ int sv_profile_read(sv_ctx *, int kind, double *total_ms /* host */, int *launch
 int sv_probe_mfma_bf16(const void *operands, size_t operand_bytes, float *sink, int iters, void *stream, double *tflops);
 int sv_probe_hbm_copy(const void *src, void *dst, size_t bytes, int reps, void *stream, double *gbs_each_way);
 int sv_probe_hbm_read(const void *src, size_t bytes, int reps, void *sink, void *stream, double *gbs);
+/* Whether the matrix unit and the vector ALU overlap: 256 work-groups of 4 * waves_per_simd (1 or 2) waves run
+ * `iters` rounds of (a) eight independent v_mfma_f32_16x16x32_bf16, (b) 8 * valu_per_mfma (2, 4 or 6) independent
+ * v_fma_f32, (c) both, the FMAs placed after each MFMA; operands in registers.  sink (DEVICE, 256 * 512 floats) takes
+ * a checksum; out_ms (HOST, 3 doubles) the three times in milliseconds.  Synchronises the stream. */
+int sv_probe_mfma_valu(float *sink, int iters, int valu_per_mfma, int waves_per_simd, void *stream, double *out_ms);
 
 /* Tuning / diagnostic knobs of a context.
  *   SV_OPT_GEMM_VARIANT  work-group tile of the row-major bf16 projections (0..2; -1 = per shape, default)

@@ -26,7 +26,7 @@ EXPORTS = [
     "verify_seq_add", "verify_seq_remove", "verify_seq_set_len", "verify_seq_len", "verify_kv_write",
     "verify_kv_read", "verify_prefill", "verify_prefill_batch", "verify_step",
     "sv_op_gemm_bf16", "sv_op_gemm_bf16_ws", "sv_op_gemm_plan", "sv_op_pack_rows", "sv_op_pack_weight", "sv_op_sample_scratch_bytes", "sv_op_sample", "sv_op_sample_static", "sv_op_moe_scratch_bytes", "sv_op_moe_ffn", "sv_op_attention", "sv_op_layer", "sv_op_rollback", "sv_set_option", "sv_seq_set_lens", "sv_profile_enable",
-    "sv_profile_read", "sv_probe_mfma_bf16", "sv_probe_hbm_copy", "sv_probe_hbm_read",
+    "sv_profile_read", "sv_probe_mfma_bf16", "sv_probe_hbm_copy", "sv_probe_hbm_read", "sv_probe_mfma_valu",
     "sv_plan_accept_prob", "sv_plan_tau", "sv_plan_decoupled", "sv_plan_best_window", "sv_fit_affine",
 ]
 
@@ -123,6 +123,7 @@ def load_library() -> C.CDLL:
     lib.sv_probe_mfma_bf16.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_double)]
     lib.sv_probe_hbm_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.POINTER(C.c_double)]
     lib.sv_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+    lib.sv_probe_mfma_valu.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double)]
     lib.sv_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
     lib.sv_plan_accept_prob.restype = C.c_double
     lib.sv_plan_accept_prob.argtypes = [C.c_double, C.c_int, C.c_int]
@@ -508,6 +509,22 @@ def probe_peaks(device="cuda:0", mfma_iters: int = 60000, copy_bytes: int = 1 <<
     if rc != 0:
         raise SvError(rc, "sv_probe_hbm_read")
     out["hbm_read_gbs"] = v.value
+    return out
+
+
+def probe_mfma_valu(iters: int = 20000, device="cuda:0") -> dict:
+    """Do matrix and vector instructions of a SIMD overlap?  Times (ms) of `iters` rounds of eight 16x16x32 bf16 MFMAs,
+    of 8 * NV FMAs, and of both woven, for NV in (2, 4, 6) and one or two waves per SIMD."""
+    dev = torch.device(device)
+    sink = torch.empty(256 * 512, dtype=torch.float32, device=dev)
+    out = {}
+    for waves in (1, 2):
+        for nv in (2, 4, 6):
+            ms = (C.c_double * 3)()
+            rc = lib().sv_probe_mfma_valu(_ptr(sink), iters, nv, waves, _stream_ptr(), ms)
+            if rc != 0:
+                raise SvError(rc, "sv_probe_mfma_valu")
+            out[f"waves_per_simd_{waves}_fma_per_mfma_{nv}"] = {"mfma_ms": ms[0], "fma_ms": ms[1], "woven_ms": ms[2]}
     return out
 
 

@@ -1,5 +1,6 @@
-// Two micro-benchmarks that give the rooflines of this very GPU, as opposed to the data sheet's: a register-only
-// bf16 MFMA loop and a plain device copy.  The benchmark reports every kernel's rate against both.
+// Micro-benchmarks that give the rooflines of this very GPU, as opposed to the data sheet's: a register-only bf16
+// MFMA loop, a plain device copy and read, and a loop that shows whether matrix and vector instructions overlap.
+// The benchmark reports every kernel's rate against the first three.
 // Declared in include/specverify_ops.h.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -38,6 +39,40 @@ __global__ __launch_bounds__(256, 1) void probe_mfma_kernel(const sv::u32x4* __r
 #pragma unroll
         for (int e = 0; e < 16; ++e) s += acc[i][e];
     sink[t] = s;
+}
+
+// Do the matrix unit and the vector ALU of a SIMD work at the same time?  MODE 0: `iters` rounds of eight independent
+// v_mfma_f32_16x16x32_bf16; MODE 1: `iters` rounds of 8 * NV independent v_fma_f32; MODE 2: both, NV FMAs after each
+// MFMA.  Operands in registers; 64 * WAVES threads per work-group give one or two waves per SIMD.
+template <int MODE, int NV>
+__global__ __launch_bounds__(512) void probe_mix_kernel(float* __restrict__ sink, int iters, float seed) {
+    floatx4 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    sv::bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(threadIdx.x * 0.001f + i); b[i] = (__bf16)(seed + i); }
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = seed + i + threadIdx.x;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            if (MODE != 1) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[m], 0, 0, 0);
+            if (MODE != 0) {
+#pragma unroll
+                for (int j = 0; j < NV; ++j) v[(m + j) & 7] = __builtin_fmaf(v[(m + j) & 7], 1.0001f, 0.5f);
+            }
+            if (MODE == 2) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, NV, 0);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3] + v[i];
+    sink[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
 // Plain copy, 16 bytes per lane, grid-stride: what a stream of reads and writes reaches on this part.
@@ -133,5 +168,40 @@ extern "C" int sv_probe_hbm_read(const void* src, size_t bytes, int reps, void* 
     });
     if (ms < 0.0) return SV_EHIP;
     *gbs = (double)bytes / (ms * 1e-3) / 1e9;
+    return SV_OK;
+}
+
+// Times, in milliseconds, of the three modes of probe_mix_kernel (MFMAs alone, FMAs alone, both woven) on 256
+// work-groups of `waves_per_simd` * 4 waves; out_ms[3].
+extern "C" int sv_probe_mfma_valu(float* sink, int iters, int valu_per_mfma, int waves_per_simd, void* stream, double* out_ms) {
+    if (!sink || !out_ms || iters <= 0 || (waves_per_simd != 1 && waves_per_simd != 2) ||
+        (valu_per_mfma != 2 && valu_per_mfma != 4 && valu_per_mfma != 6))
+        return SV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(256), block(256 * waves_per_simd);
+    auto timed = [&](auto kern, double& ms_out) -> int {
+        EventPair ev;
+        if (!ev.ok()) return SV_EHIP;
+        hipLaunchKernelGGL(kern, grid, block, 0, st, sink, iters / 8 + 1, 1.0f);       // warm-up
+        if (hipEventRecord(ev.a, st) != hipSuccess) return SV_EHIP;
+        hipLaunchKernelGGL(kern, grid, block, 0, st, sink, iters, 1.0f);
+        if (hipEventRecord(ev.b, st) != hipSuccess || hipEventSynchronize(ev.b) != hipSuccess || hipGetLastError() != hipSuccess) return SV_EHIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess) return SV_EHIP;
+        ms_out = ms;
+        return SV_OK;
+    };
+    int rc = SV_OK;
+    switch (valu_per_mfma) {
+        case 2:
+            if ((rc = timed(probe_mix_kernel<0, 2>, out_ms[0])) || (rc = timed(probe_mix_kernel<1, 2>, out_ms[1])) || (rc = timed(probe_mix_kernel<2, 2>, out_ms[2]))) return rc;
+            break;
+        case 4:
+            if ((rc = timed(probe_mix_kernel<0, 4>, out_ms[0])) || (rc = timed(probe_mix_kernel<1, 4>, out_ms[1])) || (rc = timed(probe_mix_kernel<2, 4>, out_ms[2]))) return rc;
+            break;
+        default:
+            if ((rc = timed(probe_mix_kernel<0, 6>, out_ms[0])) || (rc = timed(probe_mix_kernel<1, 6>, out_ms[1])) || (rc = timed(probe_mix_kernel<2, 6>, out_ms[2]))) return rc;
+            break;
+    }
     return SV_OK;
 }
