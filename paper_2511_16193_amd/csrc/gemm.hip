@@ -468,8 +468,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_tile_kernel(
 
     // The loop is written out instruction by instruction.  A wave alone on its SIMD issues in order, and the matrix
     // unit runs dry whenever anything else is issued in a block: with the eight LDS reads of a slice and the sixteen
-    // loads of a fill issued together it was busy 55 % of the cycles.  So one LDS read (of the next slice) or one
-    // group of loads (of the fill after next) follows each product and executes in its shadow.  The reads are
+    // loads of a fill issued together it was busy 55 % of the cycles.  So the LDS reads of the next slice and the
+    // loads of the fill after next sit between the products, one or two at a time, and execute in their shadow (the
+    // last read of a slice early enough for its data to be there when the slice ends).  The reads are
     // hand-placed instructions with hand-counted waits because a direct-to-LDS load in flight makes the compiler
     // wait for every LDS read at once.
     u32x4 af[2][4], wf[2][4];
